@@ -1,0 +1,337 @@
+"""Seeded synthetic sparse matrices (CSR, int32 indices, fp64 values) and dense x.
+
+This module only *draws inputs*: row lengths, column indices, values and the
+vector x.  It holds none of the CSR5 method's arithmetic (no tile, descriptor or
+SpMV code) so that both the CPU oracle's tests and the HIP path's tests can use
+the same inputs without sharing any implementation.
+
+The paper evaluates on matrices of the University of Florida collection
+(Section 5.2, Table 2); those are not available offline, so the five workloads
+here reproduce the *shape statistics* of its regular group (tightly clustered
+row lengths) and irregular group (power-law / a few huge rows / empty rows).
+
+Every generator returns a `Csr` whose columns are sorted and distinct inside a
+row.  All randomness comes from `numpy.random.default_rng(seed)` (PCG64).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+import numpy as np
+
+
+@dataclass
+class Csr:
+    """CSR matrix (Section 2.1): row_ptr int32[m+1], col_idx int32[nnz], val fp64[nnz]."""
+
+    m: int
+    n: int
+    row_ptr: np.ndarray
+    col_idx: np.ndarray
+    val: np.ndarray
+    x: np.ndarray
+    name: str = ""
+
+    @property
+    def nnz(self) -> int:
+        return int(self.row_ptr[-1])
+
+    def stats(self) -> dict:
+        ln = np.diff(self.row_ptr.astype(np.int64))
+        return {
+            "name": self.name, "m": self.m, "n": self.n, "nnz": self.nnz,
+            "row_len_min": int(ln.min()) if self.m else 0,
+            "row_len_avg": float(ln.mean()) if self.m else 0.0,
+            "row_len_max": int(ln.max()) if self.m else 0,
+            "empty_rows": int((ln == 0).sum()),
+        }
+
+
+def _finish(m, n, lens, cols, val, x, name) -> Csr:
+    row_ptr = np.zeros(m + 1, dtype=np.int64)
+    np.cumsum(lens, out=row_ptr[1:])
+    assert row_ptr[-1] == cols.shape[0] == val.shape[0]
+    assert row_ptr[-1] < 2 ** 31
+    return Csr(m, n, row_ptr.astype(np.int32), np.ascontiguousarray(cols, dtype=np.int32),
+               np.ascontiguousarray(val, dtype=np.float64),
+               np.ascontiguousarray(x, dtype=np.float64), name)
+
+
+def _dedupe_sorted(rows: np.ndarray, cols: np.ndarray, m: int, n: int):
+    """Sort (row, col) pairs, drop duplicates; returns (lens[m], cols sorted by row then col).
+
+    `rows` must already be non-decreasing (pairs are generated row by row).
+    """
+    key = rows.astype(np.int64) * np.int64(n) + cols.astype(np.int64)
+    key.sort()
+    if key.size:
+        keep = np.empty(key.size, dtype=bool)
+        keep[0] = True
+        np.not_equal(key[1:], key[:-1], out=keep[1:])
+        key = key[keep]
+    r = key // np.int64(n)
+    c = key - r * np.int64(n)
+    lens = np.bincount(r, minlength=m).astype(np.int64)
+    return lens, c.astype(np.int32)
+
+
+# --------------------------------------------------------------------------
+# config 1: tiny uniform
+# --------------------------------------------------------------------------
+def tiny_uniform(m=2000, n=2000, max_len=20, seed=0) -> Csr:
+    """Row lengths uniform in {0..max_len} (about 1/(max_len+1) rows empty), columns
+    drawn without replacement, values and x uniform in [-1, 1]."""
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(0, max_len + 1, size=m).astype(np.int64)
+    lens = np.minimum(lens, n)
+    cols = np.empty(int(lens.sum()), dtype=np.int32)
+    o = 0
+    for i in range(m):
+        k = int(lens[i])
+        if k:
+            cols[o:o + k] = np.sort(rng.choice(n, size=k, replace=False))
+            o += k
+    val = rng.uniform(-1.0, 1.0, size=o)
+    x = rng.uniform(-1.0, 1.0, size=n)
+    return _finish(m, n, lens, cols, val, x, f"tiny_uniform_{m}x{n}")
+
+
+# --------------------------------------------------------------------------
+# config 2: 27-point stencil on a g^3 grid
+# --------------------------------------------------------------------------
+def stencil27(g=100, seed=1) -> Csr:
+    """3-D 27-point stencil, grid points numbered x-fastest; boundary rows are
+    truncated (8..27 entries).  Centre 26.0, neighbours -1.0 + U[-0.01, 0.01];
+    x ~ U[0, 1].  nnz = (3g-2)^3."""
+    rng = np.random.default_rng(seed)
+    m = g * g * g
+    idx = np.arange(m, dtype=np.int64)
+    ix, iy, iz = idx % g, (idx // g) % g, idx // (g * g)
+    # Offsets in increasing column order: dz slowest, dx fastest.
+    valid = []
+    offs = []
+    for dz in (-1, 0, 1):
+        for dy in (-1, 0, 1):
+            for dx in (-1, 0, 1):
+                ok = ((ix + dx >= 0) & (ix + dx < g) & (iy + dy >= 0) & (iy + dy < g)
+                      & (iz + dz >= 0) & (iz + dz < g))
+                valid.append(ok)
+                offs.append(dx + dy * g + dz * g * g)
+    valid = np.stack(valid, axis=1)            # [m, 27]
+    offs = np.asarray(offs, dtype=np.int64)
+    lens = valid.sum(axis=1).astype(np.int64)
+    colmat = idx[:, None] + offs[None, :]
+    cols = colmat[valid]                        # row-major flatten keeps column order
+    centre = np.broadcast_to(offs[None, :] == 0, valid.shape)[valid]
+    nnz = cols.shape[0]
+    assert nnz == (3 * g - 2) ** 3
+    val = -1.0 + rng.uniform(-0.01, 0.01, size=nnz)
+    val[centre] = 26.0
+    x = rng.uniform(0.0, 1.0, size=m)
+    return _finish(m, m, lens, cols.astype(np.int32), val, x, f"stencil27_{g}")
+
+
+# --------------------------------------------------------------------------
+# config 3: power-law
+# --------------------------------------------------------------------------
+def powerlaw(m=2_000_000, a_len=2.0, a_col=1.5, max_len=200_000, topup_above=1000, seed=2) -> Csr:
+    """Square power-law matrix.  Row length = clip(Zipf(a_len), 1, max_len).
+    Columns = (Zipf(a_col) - 1) mod n, i.e. strongly preferential toward low ids;
+    duplicates inside a row are dropped.  Dropping shrinks the very long rows a
+    lot (few distinct values under Zipf), so rows whose target length exceeds
+    `topup_above` are topped up with uniform columns until they reach the target.
+    Values and x ~ U[0, 1]."""
+    rng = np.random.default_rng(seed)
+    n = m
+    max_len = min(max_len, n)
+    target = np.clip(rng.zipf(a_len, size=m), 1, max_len).astype(np.int64)
+    rows = np.repeat(np.arange(m, dtype=np.int64), target)
+    cols = (rng.zipf(a_col, size=rows.shape[0]) - 1) % n
+    lens, c = _dedupe_sorted(rows, cols, m, n)
+    del rows, cols
+    long_rows = np.nonzero(target > topup_above)[0]
+    if long_rows.size:
+        start = np.zeros(m + 1, dtype=np.int64)
+        np.cumsum(lens, out=start[1:])
+        pieces = []
+        prev = 0
+        for r in long_rows:
+            have = c[start[r]:start[r + 1]]
+            need = int(target[r])
+            got = np.unique(have)
+            while got.size < need:
+                extra = rng.integers(0, n, size=2 * (need - got.size) + 16)
+                got = np.unique(np.concatenate([got, extra]))
+                if got.size > need:
+                    # drop surplus from the uniform extras only (keep it simple: random subset)
+                    drop = rng.choice(got.size, size=got.size - need, replace=False)
+                    got = np.delete(got, drop)
+            pieces.append(c[start[prev]:start[r]])
+            pieces.append(got.astype(np.int32))
+            lens[r] = got.size
+            prev = r + 1
+        pieces.append(c[start[prev]:])
+        c = np.concatenate(pieces)
+    nnz = c.shape[0]
+    val = rng.uniform(0.0, 1.0, size=nnz)
+    x = rng.uniform(0.0, 1.0, size=n)
+    return _finish(m, n, lens, c, val, x, f"powerlaw_{m}")
+
+
+# --------------------------------------------------------------------------
+# config 4: rectangular LP / circuit-like
+# --------------------------------------------------------------------------
+def lp_rect(m=1_500_000, n=4_000_000, empty_frac=0.30, geo_mean=4.0, dense_frac=0.001,
+            dense_len=20_000, seed=3) -> Csr:
+    """`empty_frac` of the rows are empty, `dense_frac` have `dense_len` entries,
+    the rest have geometric lengths with mean `geo_mean`.  Uniform columns
+    (duplicates dropped), values and x ~ N(0, 1)."""
+    rng = np.random.default_rng(seed)
+    dense_len = min(dense_len, n)
+    u = rng.random(m)
+    lens_t = rng.geometric(1.0 / geo_mean, size=m).astype(np.int64)
+    lens_t = np.minimum(lens_t, n)
+    lens_t[u < empty_frac] = 0
+    lens_t[u >= 1.0 - dense_frac] = dense_len
+    rows = np.repeat(np.arange(m, dtype=np.int64), lens_t)
+    cols = rng.integers(0, n, size=rows.shape[0])
+    lens, c = _dedupe_sorted(rows, cols, m, n)
+    nnz = c.shape[0]
+    val = rng.standard_normal(nnz)
+    x = rng.standard_normal(n)
+    return _finish(m, n, lens, c, val, x, f"lp_rect_{m}x{n}")
+
+
+# --------------------------------------------------------------------------
+# config 5: large mixed
+# --------------------------------------------------------------------------
+def mixed_large(m=8_000_000, band=5000, p_band=0.8, mu=2.5, sg=1.5, seed=4,
+                chunk_rows=1_000_000) -> Csr:
+    """Each row independently: with probability `p_band` a length uniform in
+    {8..16} with columns within +-band of the diagonal (clipped to [0, n)), else
+    a length floor(lognormal(mu, sg)) clipped to [1, n] with uniform columns.
+    Duplicates inside a row are dropped.  Values and x ~ U[-1, 1].  Generated in
+    row chunks to bound memory."""
+    rng = np.random.default_rng(seed)
+    n = m
+    lens_all, cols_all = [], []
+    for r0 in range(0, m, chunk_rows):
+        r1 = min(m, r0 + chunk_rows)
+        k = r1 - r0
+        is_band = rng.random(k) < p_band
+        lb = rng.integers(8, 17, size=k).astype(np.int64)
+        ll = np.clip(np.floor(rng.lognormal(mu, sg, size=k)), 1, n).astype(np.int64)
+        lt = np.where(is_band, lb, ll)
+        rows = np.repeat(np.arange(k, dtype=np.int64), lt)
+        rb = np.repeat(is_band, lt)
+        tot = rows.shape[0]
+        cu = rng.integers(0, n, size=tot)
+        cb = rows + r0 + rng.integers(-band, band + 1, size=tot)
+        np.clip(cb, 0, n - 1, out=cb)
+        cols = np.where(rb, cb, cu)
+        lens, c = _dedupe_sorted(rows, cols, k, n)
+        lens_all.append(lens)
+        cols_all.append(c)
+    lens = np.concatenate(lens_all)
+    c = np.concatenate(cols_all)
+    nnz = c.shape[0]
+    val = rng.uniform(-1.0, 1.0, size=nnz)
+    x = rng.uniform(-1.0, 1.0, size=n)
+    return _finish(m, n, lens, c, val, x, f"mixed_large_{m}")
+
+
+# --------------------------------------------------------------------------
+# registry of the five headline workloads and their scaled-down versions
+# --------------------------------------------------------------------------
+def config(i: int, scale: float = 1.0) -> Csr:
+    """Workload i in 1..5 at full size (scale=1) or shrunk (scale<1 reduces the
+    number of rows; the per-row distributions are unchanged)."""
+    if i == 1:
+        return tiny_uniform()
+    if i == 2:
+        g = max(4, int(round(100 * scale ** (1.0 / 3.0))))
+        return stencil27(g=g)
+    if i == 3:
+        m = max(1000, int(2_000_000 * scale))
+        return powerlaw(m=m, max_len=min(200_000, m))
+    if i == 4:
+        m = max(1000, int(1_500_000 * scale))
+        nn = max(2000, int(4_000_000 * scale))
+        return lp_rect(m=m, n=nn, dense_len=min(20_000, nn // 4))
+    if i == 5:
+        m = max(20_000, int(8_000_000 * scale))
+        return mixed_large(m=m, band=min(5000, m // 4), chunk_rows=1_000_000)
+    raise ValueError(i)
+
+
+# --------------------------------------------------------------------------
+# small structured / degenerate matrices for pins and edge-case parity
+# --------------------------------------------------------------------------
+def from_row_lengths(lens, n, seed=0, name="custom", value_kind="uniform") -> Csr:
+    """Matrix with the given row lengths, uniform distinct sorted columns."""
+    rng = np.random.default_rng(seed)
+    lens = np.minimum(np.asarray(lens, dtype=np.int64), n)
+    m = lens.shape[0]
+    tot = int(lens.sum())
+    cols = np.empty(tot, dtype=np.int32)
+    o = 0
+    for i in range(m):
+        k = int(lens[i])
+        if k == 0:
+            continue
+        if k > n // 2:
+            pick = np.sort(rng.permutation(n)[:k])
+        else:
+            pick = np.unique(rng.integers(0, n, size=k))
+            while pick.size < k:
+                pick = np.unique(np.concatenate([pick, rng.integers(0, n, size=k - pick.size)]))
+        cols[o:o + k] = pick
+        o += k
+    if value_kind == "uniform":
+        val = rng.uniform(-1.0, 1.0, size=tot)
+    elif value_kind == "wide":       # magnitudes spread over many decades
+        val = rng.uniform(-1.0, 1.0, size=tot) * 10.0 ** rng.integers(-8, 9, size=tot)
+    else:
+        raise ValueError(value_kind)
+    x = rng.uniform(-1.0, 1.0, size=n)
+    return _finish(m, n, lens, cols, val, x, name)
+
+
+def identity(n) -> Csr:
+    rng = np.random.default_rng(n)
+    return _finish(n, n, np.ones(n, dtype=np.int64), np.arange(n, dtype=np.int32),
+                   np.ones(n), rng.uniform(-1, 1, size=n), f"identity_{n}")
+
+
+def permutation(n, seed=0) -> Csr:
+    rng = np.random.default_rng(seed)
+    perm = rng.permutation(n).astype(np.int32)
+    return _finish(n, n, np.ones(n, dtype=np.int64), perm, np.ones(n),
+                   rng.uniform(-1, 1, size=n), f"permutation_{n}")
+
+
+def edge_cases(T: int, seed: int = 7) -> list:
+    """Degenerate and boundary-straddling matrices for a tile of T = omega*sigma
+    nonzeros: no nonzeros, fewer than one tile, exact multiples of a tile, one
+    long row over several tiles, empty rows at the head / tail / between tiles,
+    rows shorter than sigma, identity, permutation."""
+    rng = np.random.default_rng(seed)
+    out = []
+    out.append(from_row_lengths([0] * 37, 50, seed, "all_empty"))
+    out.append(from_row_lengths([5], 40, seed, "one_short_row"))
+    out.append(from_row_lengths([T // 2, 0, 3], 2 * T, seed, "less_than_one_tile"))
+    out.append(from_row_lengths([3 * T + 17], 4 * T, seed, "one_long_row"))
+    out.append(from_row_lengths([T], T + 5, seed, "exactly_one_tile_one_row"))
+    out.append(from_row_lengths([T // 4] * 8, T, seed, "exact_two_tiles"))
+    out.append(from_row_lengths([0, 0, 0, 2 * T + 3, 0, 0, 5, 0, 0, 0], 3 * T, seed, "empties_head_tail"))
+    # a row ends exactly on a tile boundary, followed by empty rows, then more rows
+    out.append(from_row_lengths([T - 7, 7, 0, 0, 0, T // 2, T // 2, 0, 9], 2 * T, seed, "empties_at_tile_boundary"))
+    out.append(from_row_lengths(np.ones(2 * T + 11, dtype=np.int64), 3 * T, seed, "all_len1"))
+    out.append(from_row_lengths(rng.integers(0, 3, size=3 * T), 4 * T, seed, "len0to2"))
+    out.append(from_row_lengths(rng.integers(0, 40, size=400), 3000, seed, "len0to39"))
+    out.append(from_row_lengths([1, 2 * T, 1, 0, T + T // 2, 0, 0, 4, 3 * T, 2], 5 * T, seed, "long_rows_mixed"))
+    out.append(from_row_lengths(rng.integers(0, 40, size=300), 2000, seed, "wide_values", value_kind="wide"))
+    # dirty first tile whose first row is row 0  ("-0" tile pointer, Section 3.3)
+    out.append(from_row_lengths([4, 0, T, 3], 2 * T, seed, "negative_zero_tile_ptr"))
+    out.append(identity(T + 13))
+    out.append(permutation(2 * T + 1, seed))
+    return out
