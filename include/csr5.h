@@ -1,0 +1,170 @@
+/*
+ * libcsr5 -- CSR5 sparse matrix-vector multiply for AMD MI355X (gfx950).
+ *
+ * C ABI.  The operation is the one the paper states in Section 1: y = A*x with
+ * A an m x n sparse matrix given in CSR (Section 2.1), computed on the CSR5
+ * format of Section 3 by the algorithm of Section 4.
+ *
+ * Every array argument is a DEVICE pointer (memory of the current HIP device)
+ * unless a comment says "host".  Indices are int32, values are fp64.  The tile
+ * width omega is fixed to 64, the wavefront width (Section 3.2); sigma, the tile
+ * height, is chosen per matrix.  T = omega*sigma nonzeros per tile,
+ * p = ceil(nnz/T) tiles, p_c = floor(nnz/T) complete tiles (Section 3.1, 3.3).
+ *
+ * Error behaviour: every function returns CSR5_OK (0) or a negative code; none
+ * aborts or throws.  On failure csr5_convert* sets *out to NULL.
+ *
+ * Streams: the *_ex calls enqueue their kernels on the given HIP stream
+ * (hipStream_t passed as void*, NULL = the default stream) and return without
+ * waiting unless stated otherwise.
+ */
+#ifndef CSR5_H
+#define CSR5_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct csr5_handle_s *csr5_handle_t; /* opaque; owned by the library */
+
+enum {
+    CSR5_OK = 0,
+    CSR5_EINVAL = -1, /* bad argument (null pointer, negative size, inconsistent row_ptr) */
+    CSR5_ENOMEM = -2, /* allocation failed or workspace too small */
+    CSR5_EHIP = -3,   /* a HIP runtime call or kernel launch failed */
+    CSR5_ERANGE = -4  /* sigma outside [CSR5_SIGMA_MIN, CSR5_SIGMA_MAX] */
+};
+
+#define CSR5_OMEGA 64
+#define CSR5_SIGMA_MIN 1
+#define CSR5_SIGMA_MAX 48
+
+/* csr5_convert_ex flags */
+#define CSR5_FLAG_NONE 0u
+#define CSR5_FLAG_NO_HOST_CHECK 1u /* skip the blocking read of row_ptr[0], row_ptr[m] */
+
+/* bits of the device-side status word reported by csr5_status */
+#define CSR5_STATUS_BAD_ROW_PTR 1u /* row_ptr decreasing or outside [0, nnz] */
+#define CSR5_STATUS_BAD_COL_IDX 2u /* a column index outside [0, n) */
+#define CSR5_STATUS_HAS_DIRTY 4u   /* informational: some tile holds an empty row */
+
+/*
+ * sigma from nnz/row (Section 3.2): the paper's four-way rule with bounds
+ * <r, s, t, u> chosen for MI355X; nnz/row is the integer quotient nnz/m.
+ * Pure host arithmetic.
+ */
+int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
+
+/*
+ * Bytes of device workspace csr5_convert_ex needs for a matrix of m rows and
+ * nnz nonzeros at the given sigma (0 = the value csr5_sigma_auto picks).  An
+ * upper bound computable on the host: tile_ptr (p+1 words) + tile_desc
+ * (p_c*W*64 words) + empty_offset_ptr (p_c+1 words) + empty_offset (at most
+ * min(m + p_c, p_c*T) words) + a status word, each rounded up to 256 bytes.
+ * Returns 0 for invalid arguments.
+ */
+size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma);
+
+/*
+ * CSR -> CSR5 (Sections 3.3-3.5; the four steps of Section 5.4).
+ *
+ *   m, n, nnz   matrix shape, all >= 0, nnz < 2^31.
+ *   row_ptr     int32[m+1], row_ptr[0] = 0, row_ptr[m] = nnz, non-decreasing.
+ *               BORROWED: read now and again by every csr5_spmv (the format
+ *               keeps it unchanged, Section 1); must outlive the handle.
+ *   col_idx     int32[nnz], values in [0, n).  MODIFIED IN PLACE: inside every
+ *   val         double[nnz].    complete tile the entries go from CSR order to
+ *               tile column-major order (Section 3.1).  The caller keeps
+ *               ownership of the memory, must keep it alive for the handle's
+ *               lifetime, and gets CSR order back with csr5_to_csr.
+ *   out         receives the handle.  The handle owns tile_ptr, tile_desc
+ *               (bit_flag, y_offset, seg_offset packed as in Section 3.5) and
+ *               empty_offset with its per-tile start array.
+ *
+ * csr5_convert picks sigma itself, allocates with hipMalloc, runs on the default
+ * stream and checks row_ptr[0] and row_ptr[m] on the host (one blocking copy).
+ *
+ * csr5_convert_ex: sigma = 0 means automatic.  If workspace != NULL the
+ * handle's arrays are carved from it (workspace_bytes must be at least
+ * csr5_workspace_bytes(m, nnz, sigma); the memory stays the caller's and must
+ * outlive the handle), and no allocation happens on the device.  With
+ * CSR5_FLAG_NO_HOST_CHECK the call does not synchronise.  Consistency of the
+ * whole row_ptr and the range of col_idx are checked on the device during
+ * conversion; read the verdict with csr5_status.
+ */
+int csr5_convert(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, int32_t *col_idx,
+                 double *val, csr5_handle_t *out);
+int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, int32_t *col_idx,
+                    double *val, int32_t sigma, void *workspace, size_t workspace_bytes,
+                    void *hip_stream, uint32_t flags, csr5_handle_t *out);
+
+/*
+ * y = A*x (Section 4: Algorithm 8 per complete tile, the tile's first and last
+ * segment added atomically, the entries after the last complete tile by a
+ * row-wise SIMD reduction).  x double[n], y double[m]; y is overwritten (rows
+ * without nonzeros get 0).  x and y must not overlap.  Asynchronous.
+ * Summation order differs from CSR order and, through the atomics, may differ
+ * between runs in the last bits.
+ */
+int csr5_spmv(csr5_handle_t h, const double *x, double *y);
+int csr5_spmv_ex(csr5_handle_t h, const double *x, double *y, void *hip_stream);
+
+/*
+ * CSR5 -> CSR (Section 3.6): transposes col_idx and val of every complete tile
+ * back to CSR order, in place.  The handle stays valid only for csr5_free.
+ */
+int csr5_to_csr(csr5_handle_t h, void *hip_stream);
+
+/* Releases the handle and whatever it allocated; never touches the caller's
+ * arrays or workspace.  NULL is accepted. */
+int csr5_free(csr5_handle_t h);
+
+/*
+ * Waits for the conversion's stream and returns the device-side status word
+ * (CSR5_STATUS_* bits) in *status (host).  BAD_* bits mean the input violated
+ * the contract; results are then undefined (but conversion stays in bounds).
+ */
+int csr5_status(csr5_handle_t h, uint32_t *status);
+
+/*
+ * Introspection (used by the parity tests).  All outputs are host scalars and
+ * may be NULL.  empty_offset_len needs the device's count and therefore waits
+ * for the conversion's stream.
+ */
+int csr5_get_info(csr5_handle_t h, int32_t *omega, int32_t *sigma, int32_t *p, int32_t *p_complete,
+                  int32_t *desc_words_per_lane, int32_t *empty_offset_len);
+
+/*
+ * Device pointers to the handle's arrays (valid until csr5_free):
+ *   tile_ptr          uint32[p+1]   bit 31 = tile holds an empty row (Section 3.3)
+ *   tile_desc         uint32[p_c*W*64]; word k of column i of tile t at (t*W+k)*64+i;
+ *                     bits [0,sigma) bit_flag, then 6 bits seg_offset, then
+ *                     ceil(log2(64*sigma)) bits y_offset (Section 3.5)
+ *   empty_offset_ptr  int32[p_c+1]  start of tile t's entries in empty_offset
+ *   empty_offset      int32[empty_offset_len] (Algorithm 7), one per segment of
+ *                     every tile whose tile_ptr has bit 31 set
+ * Any output pointer may be NULL.
+ */
+int csr5_get_arrays(csr5_handle_t h, const uint32_t **tile_ptr, const uint32_t **tile_desc,
+                    const int32_t **empty_offset_ptr, const int32_t **empty_offset);
+
+/*
+ * Copies one of the handle's arrays to HOST memory (blocking; waits for the
+ * conversion's stream).  which: 0 tile_ptr, 1 tile_desc, 2 empty_offset_ptr,
+ * 3 empty_offset.  dst_host must hold `bytes` bytes; bytes must not exceed the
+ * array's size (empty_offset: 4*empty_offset_len), else CSR5_EINVAL.
+ */
+enum { CSR5_ARRAY_TILE_PTR = 0, CSR5_ARRAY_TILE_DESC = 1, CSR5_ARRAY_EMPTY_OFFSET_PTR = 2,
+       CSR5_ARRAY_EMPTY_OFFSET = 3 };
+int csr5_read_array(csr5_handle_t h, int which, void *dst_host, size_t bytes);
+
+/* Static description of an error code. */
+const char *csr5_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSR5_H */

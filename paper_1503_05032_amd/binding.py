@@ -1,0 +1,192 @@
+"""ctypes binding of libcsr5 (include/csr5.h).  Argument marshalling only: every
+step of the conversion and of the SpMV runs in the library's HIP kernels.
+
+Functions carry the C names.  Array arguments are torch tensors on the GPU (or
+raw integer device addresses); PyTorch is used for device memory and streams
+only.  A non-zero return code raises Csr5Error unless check=False.
+
+The shared library must have been built (paper_1503_05032_amd/build.py); there
+is no fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcsr5.so")
+
+CSR5_OK, CSR5_EINVAL, CSR5_ENOMEM, CSR5_EHIP, CSR5_ERANGE = 0, -1, -2, -3, -4
+CSR5_OMEGA, CSR5_SIGMA_MIN, CSR5_SIGMA_MAX = 64, 1, 48
+CSR5_FLAG_NONE, CSR5_FLAG_NO_HOST_CHECK = 0, 1
+CSR5_STATUS_BAD_ROW_PTR, CSR5_STATUS_BAD_COL_IDX, CSR5_STATUS_HAS_DIRTY = 1, 2, 4
+CSR5_ARRAY_TILE_PTR, CSR5_ARRAY_TILE_DESC, CSR5_ARRAY_EMPTY_OFFSET_PTR, CSR5_ARRAY_EMPTY_OFFSET = 0, 1, 2, 3
+
+# every symbol include/csr5.h declares
+SYMBOLS = [
+    "csr5_sigma_auto", "csr5_workspace_bytes", "csr5_convert", "csr5_convert_ex", "csr5_spmv",
+    "csr5_spmv_ex", "csr5_to_csr", "csr5_free", "csr5_status", "csr5_get_info", "csr5_get_arrays",
+    "csr5_read_array", "csr5_strerror",
+]
+
+
+class Csr5Error(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {csr5_strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def load():
+    """Loads libcsr5.so.  torch is imported first so that the library binds to
+    the HIP runtime torch already brought into the process."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                           f"`python {os.path.join(_PKG, 'build.py')}` (there is no fallback)")
+    import torch  # noqa: F401
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, u32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_size_t
+    lib.csr5_sigma_auto.restype = i32
+    lib.csr5_sigma_auto.argtypes = [i64, i64]
+    lib.csr5_workspace_bytes.restype = sz
+    lib.csr5_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.csr5_convert.restype = C.c_int
+    lib.csr5_convert.argtypes = [i32, i32, i32, vp, vp, vp, C.POINTER(vp)]
+    lib.csr5_convert_ex.restype = C.c_int
+    lib.csr5_convert_ex.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, sz, vp, u32, C.POINTER(vp)]
+    lib.csr5_spmv.restype = C.c_int
+    lib.csr5_spmv.argtypes = [vp, vp, vp]
+    lib.csr5_spmv_ex.restype = C.c_int
+    lib.csr5_spmv_ex.argtypes = [vp, vp, vp, vp]
+    lib.csr5_to_csr.restype = C.c_int
+    lib.csr5_to_csr.argtypes = [vp, vp]
+    lib.csr5_free.restype = C.c_int
+    lib.csr5_free.argtypes = [vp]
+    lib.csr5_status.restype = C.c_int
+    lib.csr5_status.argtypes = [vp, C.POINTER(u32)]
+    lib.csr5_get_info.restype = C.c_int
+    lib.csr5_get_info.argtypes = [vp] + [C.POINTER(i32)] * 6
+    lib.csr5_get_arrays.restype = C.c_int
+    lib.csr5_get_arrays.argtypes = [vp] + [C.POINTER(vp)] * 4
+    lib.csr5_read_array.restype = C.c_int
+    lib.csr5_read_array.argtypes = [vp, C.c_int, vp, sz]
+    lib.csr5_strerror.restype = C.c_char_p
+    lib.csr5_strerror.argtypes = [C.c_int]
+    _lib = lib
+    return lib
+
+
+def _ptr(t):
+    """Device address of a torch tensor (or pass an int / None through)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t or None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous GPU tensor")
+    return t.data_ptr() or None
+
+
+def _stream(s):
+    if s is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(s, int):
+        return s or None
+    return s.cuda_stream or None
+
+
+def _chk(rc, where, check):
+    if check and rc != CSR5_OK:
+        raise Csr5Error(rc, where)
+    return rc
+
+
+def csr5_strerror(code):
+    return load().csr5_strerror(int(code)).decode()
+
+
+def csr5_sigma_auto(nnz, m):
+    return int(load().csr5_sigma_auto(int(nnz), int(m)))
+
+
+def csr5_workspace_bytes(m, nnz, sigma=0):
+    return int(load().csr5_workspace_bytes(int(m), int(nnz), int(sigma)))
+
+
+def csr5_convert(m, n, nnz, row_ptr, col_idx, val, check=True):
+    """Returns the handle (an integer).  Uses the default stream and hipMalloc."""
+    h = C.c_void_p()
+    rc = load().csr5_convert(m, n, nnz, _ptr(row_ptr), _ptr(col_idx), _ptr(val), C.byref(h))
+    _chk(rc, "csr5_convert", check)
+    return h.value if check else (rc, h.value)
+
+
+def csr5_convert_ex(m, n, nnz, row_ptr, col_idx, val, sigma=0, workspace=None, stream=None,
+                    flags=CSR5_FLAG_NONE, check=True):
+    """`workspace` is a torch uint8 GPU tensor (or None -> hipMalloc inside)."""
+    h = C.c_void_p()
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().csr5_convert_ex(m, n, nnz, _ptr(row_ptr), _ptr(col_idx), _ptr(val), int(sigma),
+                                _ptr(workspace), wsb, _stream(stream), int(flags), C.byref(h))
+    _chk(rc, "csr5_convert_ex", check)
+    return h.value if check else (rc, h.value)
+
+
+def csr5_spmv(h, x, y, check=True):
+    return _chk(load().csr5_spmv(h, _ptr(x), _ptr(y)), "csr5_spmv", check)
+
+
+def csr5_spmv_ex(h, x, y, stream=None, check=True):
+    return _chk(load().csr5_spmv_ex(h, _ptr(x), _ptr(y), _stream(stream)), "csr5_spmv_ex", check)
+
+
+def csr5_to_csr(h, stream=None, check=True):
+    return _chk(load().csr5_to_csr(h, _stream(stream)), "csr5_to_csr", check)
+
+
+def csr5_free(h, check=True):
+    return _chk(load().csr5_free(h), "csr5_free", check)
+
+
+def csr5_status(h):
+    st = C.c_uint32()
+    _chk(load().csr5_status(h, C.byref(st)), "csr5_status", True)
+    return st.value
+
+
+def csr5_get_info(h):
+    """dict(omega, sigma, p, p_complete, desc_words_per_lane, empty_offset_len)."""
+    v = [C.c_int32() for _ in range(6)]
+    _chk(load().csr5_get_info(h, *[C.byref(a) for a in v]), "csr5_get_info", True)
+    keys = ["omega", "sigma", "p", "p_complete", "desc_words_per_lane", "empty_offset_len"]
+    return {k: a.value for k, a in zip(keys, v)}
+
+
+def csr5_get_arrays(h):
+    """Device addresses: dict(tile_ptr, tile_desc, empty_offset_ptr, empty_offset)."""
+    v = [C.c_void_p() for _ in range(4)]
+    _chk(load().csr5_get_arrays(h, *[C.byref(a) for a in v]), "csr5_get_arrays", True)
+    return dict(zip(["tile_ptr", "tile_desc", "empty_offset_ptr", "empty_offset"], [a.value for a in v]))
+
+
+def csr5_read_array(h, which):
+    """Host copy (NumPy) of one of the handle's arrays."""
+    info = csr5_get_info(h)
+    count, dtype = {
+        CSR5_ARRAY_TILE_PTR: (info["p"] + 1, np.uint32),
+        CSR5_ARRAY_TILE_DESC: (info["p_complete"] * info["desc_words_per_lane"] * CSR5_OMEGA, np.uint32),
+        CSR5_ARRAY_EMPTY_OFFSET_PTR: (info["p_complete"] + 1, np.int32),
+        CSR5_ARRAY_EMPTY_OFFSET: (info["empty_offset_len"], np.int32),
+    }[which]
+    out = np.empty(count, dtype=dtype)
+    _chk(load().csr5_read_array(h, which, out.ctypes.data_as(C.c_void_p), out.nbytes),
+         "csr5_read_array", True)
+    return out

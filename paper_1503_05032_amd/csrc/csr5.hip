@@ -1,0 +1,922 @@
+// libcsr5: CSR -> CSR5 conversion and CSR5 SpMV for gfx950 (MI355X).
+//
+// Follows Liu & Vinter, "CSR5: An Efficient Storage Format for Cross-Platform
+// Sparse Matrix-Vector Multiplication" (ICS'15): format in Section 3, SpMV in
+// Section 4.  omega = 64 = one wavefront per tile, one lane per tile column.
+//
+// What is different from the paper's own GPU design, and why, is said at each
+// kernel.  The C ABI is declared in include/csr5.h.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <new>
+#include <type_traits>
+
+#include "csr5.h"
+
+namespace {
+
+constexpr int OMEGA = CSR5_OMEGA;
+constexpr int SBITS = 6;  // ceil(log2 omega)
+constexpr uint32_t DIRTY = 0x80000000u;
+constexpr uint32_t ROWMASK = 0x7fffffffu;
+constexpr uint32_t BAD_BITS = CSR5_STATUS_BAD_ROW_PTR | CSR5_STATUS_BAD_COL_IDX;
+constexpr int NUM_XCD = 8;  // MI355X: 8 accelerator dies, each with its own L2
+
+// sigma rule constants <r, s, t, u> for MI355X (Section 3.2 leaves them to the
+// hardware; see csr5_sigma_auto).
+constexpr int RULE_R = 4, RULE_S = 16, RULE_T = 256, RULE_U = 16;
+
+inline int ceil_log2_host(int64_t v) {
+    int b = 0;
+    while ((int64_t(1) << b) < v) b++;
+    return b;
+}
+
+struct Geom {
+    int32_t sigma, T, W, ybits;
+    int32_t p, pc;
+};
+
+inline Geom make_geom(int64_t nnz, int sigma) {
+    Geom g;
+    g.sigma = sigma;
+    g.T = OMEGA * sigma;
+    g.ybits = ceil_log2_host(int64_t(OMEGA) * sigma);
+    g.W = (sigma + SBITS + g.ybits + 31) / 32;
+    g.p = int32_t((nnz + g.T - 1) / g.T);
+    g.pc = int32_t(nnz / g.T);
+    return g;
+}
+
+inline size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
+
+// ----------------------------------------------------------------------------
+// device helpers
+// ----------------------------------------------------------------------------
+
+// Number of entries of a[0..len) that are <= key ("upper bound").  This is the
+// binary search of Algorithms 4 and 7: with empty rows several row_ptr entries
+// are equal, and count-1 is then the non-empty row that owns nonzero `key`.
+__device__ __forceinline__ int count_le_i32(const int32_t* __restrict__ a, int len, int64_t key) {
+    int lo = 0, hi = len;
+    while (lo < hi) {
+        int mid = lo + ((hi - lo) >> 1);
+        if (int64_t(a[mid]) <= key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// Same over tile_ptr with the empty-row bit masked off.
+__device__ __forceinline__ int count_le_tileptr(const uint32_t* a, int len, uint32_t key) {
+    int lo = 0, hi = len;
+    while (lo < hi) {
+        int mid = lo + ((hi - lo) >> 1);
+        uint32_t v = __hip_atomic_load(&a[mid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ROWMASK;
+        if (v <= key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (OMEGA - 1); }
+
+// Workgroups are dealt round-robin to the 8 XCDs.  Give every XCD one
+// contiguous range of logical blocks instead, so that neighbouring tiles (which
+// gather neighbouring parts of x) share one L2 rather than eight.
+__device__ __forceinline__ uint32_t xcd_remap(uint32_t w, uint32_t nb) {
+    uint32_t per = nb / NUM_XCD, rem = nb % NUM_XCD;
+    uint32_t xcd = w % NUM_XCD, k = w / NUM_XCD;
+    uint32_t start = xcd * per + (xcd < rem ? xcd : rem);
+    return start + k;
+}
+
+// ----------------------------------------------------------------------------
+// Conversion step 2a: tile_ptr (Algorithm 4, first loop).  One thread per
+// tile boundary.  The same launch clears the flag words the next kernel ORs
+// into, and the status word.
+// ----------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_tile_ptr(int m, const int32_t* __restrict__ row_ptr, int T, int p, uint32_t* __restrict__ tile_ptr,
+           uint32_t* __restrict__ desc, size_t ndesc, uint32_t* __restrict__ status) {
+    size_t gid = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    size_t stride = size_t(gridDim.x) * blockDim.x;
+    for (size_t k = gid; k < ndesc; k += stride) desc[k] = 0u;
+    if (gid == 0) *status = 0u;
+    for (size_t t = gid; t <= size_t(p); t += stride) {
+        int64_t bnd = int64_t(t) * T;
+        tile_ptr[t] = uint32_t(count_le_i32(row_ptr, m + 1, bnd) - 1);
+    }
+}
+
+// ----------------------------------------------------------------------------
+// Conversion steps 2b + 3a, one thread per matrix row.
+//  * empty row   -> mark the tile whose row range holds it (Algorithm 4, second
+//    loop, turned inside out: the printed loop walks each tile's rows, which
+//    serialises on a tile that spans millions of empty rows; here every empty
+//    row finds its tile by binary search over tile_ptr, same result).
+//  * other rows  -> set the bit_flag of the row's first nonzero (Section 3.4;
+//    the scatter of Algorithm 3 step 1) directly inside the packed descriptor.
+// Also validates row_ptr.
+// ----------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_rows(int m, int nnz, const int32_t* __restrict__ row_ptr, int sigma, int T, int W, int p, int pc,
+       uint32_t* tile_ptr, uint32_t* desc, uint32_t* status) {
+    int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= m) return;
+    int a = row_ptr[r], b = row_ptr[r + 1];
+    bool bad = (a < 0) || (b < a) || (b > nnz) || (r == 0 && a != 0) || (r == m - 1 && b != nnz);
+    if (bad) {
+        atomicOr(status, CSR5_STATUS_BAD_ROW_PTR);
+        return;
+    }
+    if (a == b) {
+        int t = count_le_tileptr(tile_ptr, p + 1, uint32_t(r)) - 1;
+        if (t >= 0 && t < p) {
+            uint32_t old = atomicOr(&tile_ptr[t], DIRTY);
+            if (!(old & DIRTY)) atomicOr(status, CSR5_STATUS_HAS_DIRTY);
+        }
+    } else if (int64_t(a) < int64_t(pc) * T) {
+        int tile = a / T;
+        int w = a - tile * T;
+        int i = w / sigma;
+        int j = w - i * sigma;
+        atomicOr(&desc[(size_t(tile) * W + (j >> 5)) * OMEGA + i], 1u << (j & 31));
+    }
+}
+
+// ----------------------------------------------------------------------------
+// Conversion step 3b, one wavefront per complete tile, lane = tile column:
+// forced first flag, y_offset = exclusive scan of the columns' flag counts,
+// seg_offset = run of flag-less columns to the right (Algorithm 5; the scan and
+// the run length are wavefront operations here), packing (Section 3.5), and the
+// tile's segment count for the empty_offset layout.
+// ----------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_tile_desc(int sigma, int W, int ybits, int pc, const uint32_t* __restrict__ tile_ptr,
+            uint32_t* __restrict__ desc, int32_t* __restrict__ eop) {
+    int tile = blockIdx.x * (blockDim.x / OMEGA) + (threadIdx.x / OMEGA);
+    if (tile >= pc) return;
+    int lane = lane_id();
+    size_t base = size_t(tile) * W * OMEGA + lane;
+    uint64_t flags = desc[base];
+    if (sigma > 32) flags |= uint64_t(desc[base + OMEGA]) << 32;
+    if (lane == 0) flags |= 1u;
+    int cnt = __popcll(flags);
+    int incl = cnt;
+#pragma unroll
+    for (int d = 1; d < OMEGA; d <<= 1) {
+        int up = __shfl_up(incl, d, OMEGA);
+        if (lane >= d) incl += up;
+    }
+    uint32_t yo = uint32_t(incl - cnt);
+    int total = __shfl(incl, OMEGA - 1, OMEGA);
+    uint64_t heads = __ballot(cnt > 0);
+    uint64_t right = (lane == OMEGA - 1) ? 0ull : (heads >> (lane + 1));
+    uint32_t so = 0;
+    if (cnt > 0) so = right ? uint32_t(__builtin_ctzll(right)) : uint32_t(OMEGA - 1 - lane);
+    // little-endian bit field: flags | seg_offset << sigma | y_offset << (sigma+6)
+    int ysh = sigma + SBITS;  // <= 54
+    uint64_t lo = flags | (uint64_t(so) << sigma) | (uint64_t(yo) << ysh);
+    uint64_t hi = (ysh + ybits > 64) ? (uint64_t(yo) >> (64 - ysh)) : 0ull;
+    desc[base] = uint32_t(lo);
+    if (W > 1) desc[base + OMEGA] = uint32_t(lo >> 32);
+    if (W > 2) desc[base + 2 * OMEGA] = uint32_t(hi);
+    if (lane == 0) eop[tile] = (tile_ptr[tile] & DIRTY) ? total : 0;
+}
+
+// ----------------------------------------------------------------------------
+// empty_offset layout: exclusive prefix sum of the per-tile segment counts
+// (non-zero only for tiles with an empty row).  One workgroup; the array has
+// p_c + 1 entries.  Skipped when no tile is marked.
+// ----------------------------------------------------------------------------
+constexpr int SCAN_THREADS = 1024, SCAN_ITEMS = 8;
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_scan_eop(int pc, int32_t* __restrict__ eop, const uint32_t* __restrict__ status) {
+    if (!(*status & CSR5_STATUS_HAS_DIRTY)) {
+        if (threadIdx.x == 0) eop[pc] = 0;
+        return;
+    }
+    __shared__ int wave_sum[SCAN_THREADS / OMEGA];
+    __shared__ int chunk_total;
+    int lane = lane_id(), wave = threadIdx.x / OMEGA;
+    int carry = 0;
+    for (int base = 0; base < pc; base += SCAN_THREADS * SCAN_ITEMS) {
+        int idx0 = base + threadIdx.x * SCAN_ITEMS;
+        int local[SCAN_ITEMS];
+        int s = 0;
+#pragma unroll
+        for (int q = 0; q < SCAN_ITEMS; q++) {
+            int v = (idx0 + q < pc) ? eop[idx0 + q] : 0;
+            local[q] = s;
+            s += v;
+        }
+        int incl = s;
+#pragma unroll
+        for (int d = 1; d < OMEGA; d <<= 1) {
+            int up = __shfl_up(incl, d, OMEGA);
+            if (lane >= d) incl += up;
+        }
+        if (lane == OMEGA - 1) wave_sum[wave] = incl;
+        __syncthreads();
+        if (wave == 0) {
+            int v = (lane < SCAN_THREADS / OMEGA) ? wave_sum[lane] : 0;
+            int ws = v;
+#pragma unroll
+            for (int d = 1; d < SCAN_THREADS / OMEGA; d <<= 1) {
+                int up = __shfl_up(ws, d, OMEGA);
+                if (lane >= d) ws += up;
+            }
+            if (lane < SCAN_THREADS / OMEGA) wave_sum[lane] = ws - v;  // exclusive
+            if (lane == SCAN_THREADS / OMEGA - 1) chunk_total = ws;
+        }
+        __syncthreads();
+        int excl = carry + wave_sum[wave] + incl - s;
+#pragma unroll
+        for (int q = 0; q < SCAN_ITEMS; q++)
+            if (idx0 + q < pc) eop[idx0 + q] = excl + local[q];
+        carry += chunk_total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) eop[pc] = carry;
+}
+
+// ----------------------------------------------------------------------------
+// empty_offset values (Algorithm 7), one thread per matrix row instead of one
+// sequential walk per tile: a non-empty row whose first nonzero lies in a
+// marked complete tile is segment number  y_offset[column] + (flags below it in
+// the column)  of that tile, and its entry is  row - tile_ptr.  Segment 0 of a
+// marked tile may start with the forced flag (a row continued from the previous
+// tile, which is then the tile's first row): its entry is 0 and is written by
+// the extra p_c threads at the end of the grid.
+// ----------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_empty_offset(int m, const int32_t* __restrict__ row_ptr, int sigma, int T, int W, int pc,
+               const uint32_t* __restrict__ tile_ptr, const uint32_t* __restrict__ desc,
+               const int32_t* __restrict__ eop, int32_t* __restrict__ eo,
+               const uint32_t* __restrict__ status) {
+    uint32_t st = *status;
+    if (!(st & CSR5_STATUS_HAS_DIRTY) || (st & BAD_BITS)) return;
+    int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (g >= int64_t(m)) {
+        int64_t t = g - m;
+        if (t < pc && (tile_ptr[t] & DIRTY)) eo[eop[t]] = 0;
+        return;
+    }
+    int r = int(g);
+    int a = row_ptr[r], b = row_ptr[r + 1];
+    if (a == b || int64_t(a) >= int64_t(pc) * T) return;
+    int tile = a / T;
+    uint32_t tp = tile_ptr[tile];
+    if (!(tp & DIRTY)) return;
+    int w = a - tile * T;
+    int i = w / sigma;
+    int j = w - i * sigma;
+    size_t base = size_t(tile) * W * OMEGA + i;
+    uint64_t lo = desc[base];
+    if (W > 1) lo |= uint64_t(desc[base + OMEGA]) << 32;
+    uint64_t hi = (W > 2) ? desc[base + 2 * OMEGA] : 0u;
+    int ysh = sigma + SBITS;
+    uint64_t yo = lo >> ysh;
+    if (W > 2) yo |= hi << (64 - ysh);
+    // y_offset occupies every bit above seg_offset (unused high bits are zero)
+    uint64_t below = lo & ((uint64_t(1) << j) - 1);
+    int seg = int(yo) + __popcll(below);
+    eo[eop[tile] + seg] = r - int(tp & ROWMASK);
+}
+
+// ----------------------------------------------------------------------------
+// Conversion step 4 (Section 3.1): in-place transposition of col_idx and val
+// inside every complete tile, one wavefront per tile.  The tile is read in CSR
+// order (lane-contiguous), parked in LDS, and written back column-major
+// (lane-contiguous again), so both HBM directions are fully coalesced and each
+// lane happens to write exactly the addresses it read.  LDS rows are padded to
+// an odd pitch to avoid bank conflicts on the strided LDS read.  BACK = the
+// inverse permutation (CSR5 -> CSR, Section 3.6).  The last block also checks
+// the column indices of the incomplete tile.
+// ----------------------------------------------------------------------------
+template <int SIGMA>
+struct TransposeShape {
+    // tiles (= wavefronts) per workgroup, chosen so the LDS buffer stays under 40 KB
+    static constexpr int WAVES = SIGMA <= 16 ? 4 : (SIGMA <= 32 ? 2 : 1);
+    static constexpr int PITCH = SIGMA | 1;
+};
+
+template <int SIGMA, bool BACK>
+__global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
+k_transpose(int pc, int n, int nnz, int32_t* __restrict__ col_idx, double* __restrict__ val,
+            uint32_t* __restrict__ status) {
+    constexpr int T = OMEGA * SIGMA;
+    constexpr int PITCH = TransposeShape<SIGMA>::PITCH;
+    constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
+    __shared__ double lds[WAVES][OMEGA * PITCH];
+    const int wave = threadIdx.x / OMEGA, lane = lane_id();
+    const int tile = blockIdx.x * WAVES + wave;
+    const bool active = tile < pc;                 // uniform per wavefront
+    const size_t base = size_t(active ? tile : 0) * T;
+    double* buf = lds[wave];
+    int32_t* ibuf = reinterpret_cast<int32_t*>(buf);
+    bool bad = false;
+
+    // ---- val: HBM -> registers -> LDS -> registers -> HBM
+    double v[SIGMA];
+    if (active) {
+#pragma unroll
+        for (int k = 0; k < SIGMA; k++) v[k] = __builtin_nontemporal_load(&val[base + k * OMEGA + lane]);
+        if (!BACK) {
+#pragma unroll
+            for (int k = 0; k < SIGMA; k++) {
+                int e = k * OMEGA + lane;          // CSR offset inside the tile
+                buf[(e / SIGMA) * PITCH + (e % SIGMA)] = v[k];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < SIGMA; j++) buf[lane * PITCH + j] = v[j];
+        }
+    }
+    __syncthreads();
+    if (active) {
+        if (!BACK) {
+#pragma unroll
+            for (int j = 0; j < SIGMA; j++) v[j] = buf[lane * PITCH + j];
+        } else {
+#pragma unroll
+            for (int k = 0; k < SIGMA; k++) {
+                int e = k * OMEGA + lane;
+                v[k] = buf[(e / SIGMA) * PITCH + (e % SIGMA)];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < SIGMA; k++) __builtin_nontemporal_store(v[k], &val[base + k * OMEGA + lane]);
+    }
+    __syncthreads();
+    // ---- col_idx, same path through the same LDS buffer
+    int32_t c[SIGMA];
+    if (active) {
+#pragma unroll
+        for (int k = 0; k < SIGMA; k++) {
+            c[k] = __builtin_nontemporal_load(&col_idx[base + k * OMEGA + lane]);
+            bad |= (c[k] < 0) | (c[k] >= n);
+        }
+        if (!BACK) {
+#pragma unroll
+            for (int k = 0; k < SIGMA; k++) {
+                int e = k * OMEGA + lane;
+                ibuf[(e / SIGMA) * PITCH + (e % SIGMA)] = c[k];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < SIGMA; j++) ibuf[lane * PITCH + j] = c[j];
+        }
+    }
+    __syncthreads();
+    if (active) {
+        if (!BACK) {
+#pragma unroll
+            for (int j = 0; j < SIGMA; j++) c[j] = ibuf[lane * PITCH + j];
+        } else {
+#pragma unroll
+            for (int k = 0; k < SIGMA; k++) {
+                int e = k * OMEGA + lane;
+                c[k] = ibuf[(e / SIGMA) * PITCH + (e % SIGMA)];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < SIGMA; k++) __builtin_nontemporal_store(c[k], &col_idx[base + k * OMEGA + lane]);
+    }
+    if (!BACK && blockIdx.x == gridDim.x - 1) {
+        for (size_t e = size_t(pc) * T + threadIdx.x; e < size_t(nnz); e += blockDim.x) {
+            int32_t ce = col_idx[e];
+            bad |= (ce < 0) | (ce >= n);
+        }
+    }
+    if (!BACK && bad) atomicOr(status, CSR5_STATUS_BAD_COL_IDX);
+}
+
+// ----------------------------------------------------------------------------
+// y <- 0.  The tiles add their first and last segment atomically (Section 4),
+// and rows without nonzeros are never stored by any tile, so y starts at zero.
+// A fill kernel rather than a memset node, so that callers may capture
+// csr5_spmv into a HIP graph.
+// ----------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_zero_f64(double* __restrict__ y, size_t m) {
+    size_t gid = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    size_t stride = size_t(gridDim.x) * blockDim.x;
+    // two doubles per store where alignment allows
+    size_t m2 = m / 2;
+    if ((reinterpret_cast<uintptr_t>(y) & 15) == 0) {
+        double2* y2 = reinterpret_cast<double2*>(y);
+        for (size_t k = gid; k < m2; k += stride) y2[k] = make_double2(0.0, 0.0);
+        if (gid == 0 && (m & 1)) y[m - 1] = 0.0;
+    } else {
+        for (size_t k = gid; k < m; k += stride) y[k] = 0.0;
+    }
+}
+
+// ----------------------------------------------------------------------------
+// CSR5 SpMV (Algorithm 8), one wavefront per complete tile, lane i = column i.
+//
+// Lane i streams its sigma (val, col_idx) pairs -- at each step j the 64 lanes
+// read 64 consecutive entries -- gathers x, and walks its bit_flag word: a set
+// flag closes the running sum either as the column's "red" head (belongs to a
+// segment opened by an earlier column) or as a "green" complete segment that is
+// stored straight to y[tile_ptr + y_offset + k].  What follows the last flag is
+// the "blue" tail.
+//
+// In-tile segmented sum (Algorithm 8 line 22).  Algorithm 6 computes it as a
+// difference of two prefix sums over the whole tile, which loses the accuracy
+// of a small row sitting after large ones.  Here: red partials are shifted one
+// lane down (tmp[i] = red[i+1], the printed tmp[i-1] <- sum) and summed by a
+// segmented suffix scan made of six wavefront shuffles, the segments being
+// delimited by the ballot of "column has a flag".  The range it sums for a head
+// column i is exactly tmp[i .. i+seg_offset[i]], the value Algorithm 6 defines;
+// seg_offset itself is not read (the ballot carries the same information).
+//
+// Cross-tile (Section 4): segment 0 of a tile may continue a row opened by the
+// previous tile and the last segment may be continued by the next one; both are
+// added with a hardware fp64 atomic onto the zeroed y.  All other segments are
+// owned by this tile and are plain stores.
+//
+// The extra last workgroup handles the entries after the last complete tile.
+// ----------------------------------------------------------------------------
+template <int SIGMA>
+struct FlagWord {
+    using type = typename std::conditional<(SIGMA > 32), uint64_t, uint32_t>::type;
+};
+
+__device__ __forceinline__ void atomic_add_f64(double* addr, double v) {
+    // gfx950 has a native global fp64 atomic add; no return value needed
+    __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ void spmv_tail(int m, int nnz, int64_t first_entry, uint32_t tile_ptr_last,
+                          const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                          const double* __restrict__ val, const double* __restrict__ x,
+                          double* __restrict__ y) {
+    // CSR-vector in spirit (Section 4, last paragraph): 64 consecutive entries
+    // per wavefront, a shuffle reduction over runs of equal row, one atomic per
+    // run (the first row may be shared with the last complete tile).  Rows are
+    // found per entry by binary search so that trailing empty rows cost nothing.
+    int lane = lane_id();
+    int row_lo = int(tile_ptr_last & ROWMASK);
+    if (row_lo > m) row_lo = m;
+    int64_t span = int64_t(nnz) - first_entry;
+    int64_t rounds = (span + blockDim.x - 1) / blockDim.x;
+    for (int64_t it = 0; it < rounds; it++) {
+        int64_t e = first_entry + it * blockDim.x + threadIdx.x;
+        bool live = e < int64_t(nnz);
+        int row = -1;
+        double prod = 0.0;
+        if (live) {
+            row = row_lo + count_le_i32(row_ptr + row_lo, m + 1 - row_lo, e) - 1;
+            prod = val[e] * x[col_idx[e]];
+        }
+#pragma unroll
+        for (int d = 1; d < OMEGA; d <<= 1) {
+            double up = __shfl_up(prod, d, OMEGA);
+            int rup = __shfl_up(row, d, OMEGA);
+            if (lane >= d && rup == row) prod += up;
+        }
+        int rnext = __shfl_down(row, 1, OMEGA);
+        bool last_of_run = (lane == OMEGA - 1) || (rnext != row);
+        if (live && last_of_run && row >= 0 && row < m) atomic_add_f64(&y[row], prod);
+    }
+}
+
+template <int SIGMA>
+__global__ void __launch_bounds__(256)
+k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, const int32_t* __restrict__ row_ptr,
+       const uint32_t* __restrict__ tile_ptr, const uint32_t* __restrict__ tile_desc,
+       const int32_t* __restrict__ eop, const int32_t* __restrict__ eo,
+       const int32_t* __restrict__ col_idx, const double* __restrict__ val,
+       const double* __restrict__ x, double* __restrict__ y, const uint32_t* __restrict__ status) {
+    constexpr int T = OMEGA * SIGMA;
+    constexpr int YBITS = 32 - __builtin_clz(uint32_t(T - 1));        // ceil(log2(64*sigma))
+    constexpr int W = (SIGMA + SBITS + YBITS + 31) / 32;
+    constexpr int YSH = SIGMA + SBITS;
+    constexpr int WAVES = 4;
+    using flag_t = typename FlagWord<SIGMA>::type;
+
+    const uint32_t st = *status;      // consulted below, after the streaming loads are in flight
+
+    if (blockIdx.x >= nb_tiles) {     // the one extra workgroup: incomplete last tile
+        if (st & BAD_BITS) return;
+        spmv_tail(m, nnz, int64_t(pc) * T, tile_ptr[pc], row_ptr, col_idx, val, x, y);
+        return;
+    }
+    int lane = lane_id();
+    int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / OMEGA);
+    int tile = int(xcd_remap(blockIdx.x, nb_tiles)) * WAVES + wave;
+    if (tile >= pc) return;
+
+    // ---- descriptor
+    uint32_t tp = tile_ptr[tile];
+    bool dirty = (tp & DIRTY) != 0;
+    uint32_t row0 = tp & ROWMASK;
+    const uint32_t* dp = tile_desc + size_t(tile) * W * OMEGA + lane;
+    uint64_t lo = __builtin_nontemporal_load(dp);
+    if (W > 1) lo |= uint64_t(__builtin_nontemporal_load(dp + OMEGA)) << 32;
+    uint64_t hi = 0;
+    if (W > 2) hi = __builtin_nontemporal_load(dp + 2 * OMEGA);
+    constexpr int FLAG_BITS = 8 * int(sizeof(flag_t));
+    constexpr flag_t FLAG_MASK = (SIGMA == FLAG_BITS) ? ~flag_t(0) : flag_t((flag_t(1) << (SIGMA % FLAG_BITS)) - 1);
+    flag_t flags = flag_t(lo) & FLAG_MASK;
+    uint32_t yo = uint32_t(lo >> YSH);
+    if (W > 2) yo |= uint32_t(hi << (64 - YSH));
+    // empty_offset slice of a tile that holds empty rows (Algorithm 8 line 4)
+    const int32_t* eo_t = nullptr;
+    uint32_t nseg_t = 0;
+    if (dirty) {
+        int32_t e0 = eop[tile], e1 = eop[tile + 1];
+        eo_t = eo + e0;
+        nseg_t = uint32_t(e1 - e0);
+    }
+
+    // ---- stream the tile and gather x
+    const size_t base = size_t(tile) * T + lane;
+    int32_t c[SIGMA];
+    double v[SIGMA];
+#pragma unroll
+    for (int j = 0; j < SIGMA; j++) c[j] = __builtin_nontemporal_load(&col_idx[base + j * OMEGA]);
+#pragma unroll
+    for (int j = 0; j < SIGMA; j++) v[j] = __builtin_nontemporal_load(&val[base + j * OMEGA]);
+    if (st & BAD_BITS) return;        // conversion rejected the input: gather and store nothing
+    double xv[SIGMA];
+#pragma unroll
+    for (int j = 0; j < SIGMA; j++) xv[j] = x[c[j]];
+
+    // Row of segment number s of this tile.  The bound checks cannot fail for a
+    // consistent descriptor; they keep a corrupted one from writing outside y.
+    auto seg_row = [&](uint32_t s) -> uint32_t {
+        if (!dirty) return row0 + s;
+        return s < nseg_t ? row0 + uint32_t(eo_t[s]) : uint32_t(m);
+    };
+
+    // ---- per-column walk
+    double sum = 0.0, red = 0.0;
+    bool seen = false;
+    uint32_t seg = yo;
+#pragma unroll
+    for (int j = 0; j < SIGMA; j++) {
+        if ((flags >> j) & 1) {
+            if (seen) {                                   // a green segment ends
+                uint32_t row = seg_row(seg);
+                if (row < uint32_t(m)) {
+                    if (seg == 0) atomic_add_f64(&y[row], sum); else y[row] = sum;
+                }
+                seg++;
+            } else {                                      // the red head ends (empty when j == 0)
+                red = sum;
+                seen = true;
+            }
+            sum = 0.0;
+        }
+        sum = fma(v[j], xv[j], sum);
+    }
+    double blue = sum;
+    if (!seen) { red = sum; blue = 0.0; }                 // whole column is red
+
+    // ---- in-tile segmented sum of the red partials
+    uint64_t heads = __ballot(seen);                      // bit 0 is always set
+    double tmp = __shfl_down(red, 1, OMEGA);
+    if (lane == OMEGA - 1) tmp = 0.0;
+    uint64_t right = (lane == OMEGA - 1) ? 0ull : (heads >> (lane + 1));
+    int end = right ? (lane + __builtin_ctzll(right)) : (OMEGA - 1);   // last lane of my segment
+#pragma unroll
+    for (int d = 1; d < OMEGA; d <<= 1) {
+        double dn = __shfl_down(tmp, d, OMEGA);
+        if (lane + d <= end) tmp += dn;
+    }
+    if (seen) {
+        double total = blue + tmp;
+        uint32_t row = seg_row(seg);
+        bool last_head = (right == 0);                    // the tile's last segment
+        if (row < uint32_t(m)) {
+            if (seg == 0 || last_head) atomic_add_f64(&y[row], total); else y[row] = total;
+        }
+    }
+}
+
+template <int SIGMA>
+hipError_t launch_spmv(const Geom& g, int m, int nnz, const int32_t* row_ptr, const uint32_t* tile_ptr,
+                       const uint32_t* tile_desc, const int32_t* eop, const int32_t* eo,
+                       const int32_t* col_idx, const double* val, const double* x, double* y,
+                       const uint32_t* status, hipStream_t s) {
+    uint32_t nb_tiles = uint32_t((g.pc + 3) / 4);
+    uint32_t nb = nb_tiles + ((int64_t(g.pc) * g.T < nnz) ? 1u : 0u);
+    if (nb == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_spmv<SIGMA>, dim3(nb), dim3(256), 0, s, m, nnz, g.pc, nb_tiles, row_ptr,
+                       tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, status);
+    return hipGetLastError();
+}
+
+template <int SIGMA, bool BACK>
+hipError_t launch_transpose(const Geom& g, int n, int nnz, int32_t* col_idx, double* val,
+                            uint32_t* status, hipStream_t s) {
+    constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
+    uint32_t nb = uint32_t((g.pc + WAVES - 1) / WAVES);
+    if (nb == 0) nb = BACK ? 0 : 1;   // forward pass still validates the tail's columns
+    if (nb == 0) return hipSuccess;
+    hipLaunchKernelGGL((k_transpose<SIGMA, BACK>), dim3(nb), dim3(WAVES * OMEGA), 0, s, g.pc, n, nnz,
+                       col_idx, val, status);
+    return hipGetLastError();
+}
+
+#define CSR5_FOR_SIGMA(X)                                                                          \
+    X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17)   \
+    X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25) X(26) X(27) X(28) X(29) X(30) X(31) X(32)      \
+    X(33) X(34) X(35) X(36) X(37) X(38) X(39) X(40) X(41) X(42) X(43) X(44) X(45) X(46) X(47) X(48)
+
+}  // namespace
+
+// ----------------------------------------------------------------------------
+// handle
+// ----------------------------------------------------------------------------
+struct csr5_handle_s {
+    int32_t m, n, nnz;
+    Geom g;
+    const int32_t* row_ptr;
+    int32_t* col_idx;
+    double* val;
+    uint32_t* tile_ptr;
+    uint32_t* tile_desc;
+    int32_t* eop;
+    int32_t* eo;
+    uint32_t* status;
+    void* owned;           // hipMalloc'ed block, or NULL when a workspace was given
+    hipStream_t conv_stream;
+    bool in_csr5_order;
+};
+
+namespace {
+
+struct Layout {
+    size_t off_tile_ptr, off_desc, off_eop, off_eo, off_status, total;
+    size_t ndesc, eo_cap;
+};
+
+Layout make_layout(int32_t m, const Geom& g) {
+    Layout L;
+    L.ndesc = size_t(g.pc) * g.W * OMEGA;
+    size_t cap_a = size_t(m) + size_t(g.pc);
+    size_t cap_b = size_t(g.pc) * g.T;
+    L.eo_cap = cap_a < cap_b ? cap_a : cap_b;
+    size_t o = 0;
+    L.off_tile_ptr = o; o += align256((size_t(g.p) + 1) * 4);
+    L.off_desc = o;     o += align256(L.ndesc * 4);
+    L.off_eop = o;      o += align256((size_t(g.pc) + 1) * 4);
+    L.off_eo = o;       o += align256(L.eo_cap * 4);
+    L.off_status = o;   o += 256;
+    L.total = o;
+    return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* csr5_strerror(int code) {
+    switch (code) {
+        case CSR5_OK: return "ok";
+        case CSR5_EINVAL: return "invalid argument";
+        case CSR5_ENOMEM: return "out of memory or workspace too small";
+        case CSR5_EHIP: return "HIP runtime error";
+        case CSR5_ERANGE: return "sigma out of range";
+        default: return "unknown error";
+    }
+}
+
+int32_t csr5_sigma_auto(int64_t nnz, int64_t m) {
+    if (m <= 0 || nnz <= 0) return RULE_R;
+    int64_t q = nnz / m;
+    if (q <= RULE_R) return RULE_R;
+    if (q <= RULE_S) return int32_t(q);
+    if (q <= RULE_T) return RULE_S;
+    return RULE_U;
+}
+
+size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma) {
+    if (m < 0 || nnz < 0) return 0;
+    if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
+    if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX) return 0;
+    Geom g = make_geom(nnz, sigma);
+    return make_layout(m, g).total;
+}
+
+int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
+                    double* val, int32_t sigma, void* workspace, size_t workspace_bytes,
+                    void* hip_stream, uint32_t flags, csr5_handle_t* out) {
+    if (!out) return CSR5_EINVAL;
+    *out = nullptr;
+    if (m < 0 || n < 0 || nnz < 0) return CSR5_EINVAL;
+    if (!row_ptr) return CSR5_EINVAL;                      // row_ptr has m+1 >= 1 entries
+    if (nnz > 0 && (!col_idx || !val || m == 0 || n == 0)) return CSR5_EINVAL;
+    if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
+    if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX) return CSR5_ERANGE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    if (!(flags & CSR5_FLAG_NO_HOST_CHECK)) {
+        int32_t ends[2] = {0, nnz};
+        if (hipMemcpyAsync(&ends[0], row_ptr, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return CSR5_EHIP;
+        if (hipMemcpyAsync(&ends[1], row_ptr + m, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return CSR5_EHIP;
+        if (hipStreamSynchronize(s) != hipSuccess) return CSR5_EHIP;
+        if (ends[0] != 0 || ends[1] != nnz) return CSR5_EINVAL;
+    }
+
+    Geom g = make_geom(nnz, sigma);
+    Layout L = make_layout(m, g);
+    csr5_handle_s* h = new (std::nothrow) csr5_handle_s();
+    if (!h) return CSR5_ENOMEM;
+    char* basep = nullptr;
+    if (workspace) {
+        if (workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
+            delete h;
+            return workspace_bytes < L.total ? CSR5_ENOMEM : CSR5_EINVAL;
+        }
+        basep = static_cast<char*>(workspace);
+        h->owned = nullptr;
+    } else {
+        void* ptr = nullptr;
+        if (hipMalloc(&ptr, L.total) != hipSuccess) {
+            (void)hipGetLastError();
+            delete h;
+            return CSR5_ENOMEM;
+        }
+        basep = static_cast<char*>(ptr);
+        h->owned = ptr;
+    }
+    h->m = m; h->n = n; h->nnz = nnz; h->g = g;
+    h->row_ptr = row_ptr; h->col_idx = col_idx; h->val = val;
+    h->tile_ptr = reinterpret_cast<uint32_t*>(basep + L.off_tile_ptr);
+    h->tile_desc = reinterpret_cast<uint32_t*>(basep + L.off_desc);
+    h->eop = reinterpret_cast<int32_t*>(basep + L.off_eop);
+    h->eo = reinterpret_cast<int32_t*>(basep + L.off_eo);
+    h->status = reinterpret_cast<uint32_t*>(basep + L.off_status);
+    h->conv_stream = s;
+    h->in_csr5_order = true;
+
+    hipError_t e = hipSuccess;
+    {   // step 2a (+ clearing)
+        size_t work = L.ndesc > size_t(g.p) + 1 ? L.ndesc : size_t(g.p) + 1;
+        size_t nb = (work + 255) / 256;
+        if (nb > 8192) nb = 8192;
+        hipLaunchKernelGGL(k_tile_ptr, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p,
+                           h->tile_ptr, h->tile_desc, L.ndesc, h->status);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess && m > 0) {   // steps 2b + 3a
+        hipLaunchKernelGGL(k_rows, dim3(uint32_t((size_t(m) + 255) / 256)), dim3(256), 0, s, m, nnz,
+                           row_ptr, g.sigma, g.T, g.W, g.p, g.pc, h->tile_ptr, h->tile_desc, h->status);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess && g.pc > 0) {   // step 3b
+        hipLaunchKernelGGL(k_tile_desc, dim3(uint32_t((g.pc + 3) / 4)), dim3(256), 0, s, g.sigma, g.W,
+                           g.ybits, g.pc, h->tile_ptr, h->tile_desc, h->eop);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(k_scan_eop, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, h->eop, h->status);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess && g.pc > 0 && m > 0) {
+        size_t threads = size_t(m) + size_t(g.pc);
+        hipLaunchKernelGGL(k_empty_offset, dim3(uint32_t((threads + 255) / 256)), dim3(256), 0, s, m,
+                           row_ptr, g.sigma, g.T, g.W, g.pc, h->tile_ptr, h->tile_desc, h->eop, h->eo,
+                           h->status);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess && nnz > 0) {   // step 4
+        switch (sigma) {
+#define X(S) case S: e = launch_transpose<S, false>(g, n, nnz, col_idx, val, h->status, s); break;
+            CSR5_FOR_SIGMA(X)
+#undef X
+            default: e = hipErrorInvalidValue;
+        }
+    }
+    if (e != hipSuccess) {
+        (void)hipStreamSynchronize(s);
+        if (h->owned) (void)hipFree(h->owned);
+        delete h;
+        return CSR5_EHIP;
+    }
+    *out = h;
+    return CSR5_OK;
+}
+
+int csr5_convert(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
+                 double* val, csr5_handle_t* out) {
+    return csr5_convert_ex(m, n, nnz, row_ptr, col_idx, val, 0, nullptr, 0, nullptr, CSR5_FLAG_NONE, out);
+}
+
+int csr5_spmv_ex(csr5_handle_t h, const double* x, double* y, void* hip_stream) {
+    if (!h || !h->in_csr5_order) return CSR5_EINVAL;
+    if (h->m > 0 && !y) return CSR5_EINVAL;
+    if (h->nnz > 0 && !x) return CSR5_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (h->m == 0) return CSR5_OK;
+    {
+        size_t nb = (size_t(h->m) / 2 + 255) / 256;
+        if (nb == 0) nb = 1;
+        if (nb > 4096) nb = 4096;
+        hipLaunchKernelGGL(k_zero_f64, dim3(uint32_t(nb)), dim3(256), 0, s, y, size_t(h->m));
+        if (hipGetLastError() != hipSuccess) return CSR5_EHIP;
+    }
+    if (h->nnz == 0) return CSR5_OK;
+    hipError_t e;
+    switch (h->g.sigma) {
+#define X(S) case S: e = launch_spmv<S>(h->g, h->m, h->nnz, h->row_ptr, h->tile_ptr, h->tile_desc, h->eop, \
+                                        h->eo, h->col_idx, h->val, x, y, h->status, s); break;
+        CSR5_FOR_SIGMA(X)
+#undef X
+        default: e = hipErrorInvalidValue;
+    }
+    return e == hipSuccess ? CSR5_OK : CSR5_EHIP;
+}
+
+int csr5_spmv(csr5_handle_t h, const double* x, double* y) { return csr5_spmv_ex(h, x, y, nullptr); }
+
+int csr5_to_csr(csr5_handle_t h, void* hip_stream) {
+    if (!h) return CSR5_EINVAL;
+    if (!h->in_csr5_order) return CSR5_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipSuccess;
+    if (h->nnz > 0) {
+        switch (h->g.sigma) {
+#define X(S) case S: e = launch_transpose<S, true>(h->g, h->n, h->nnz, h->col_idx, h->val, h->status, s); break;
+            CSR5_FOR_SIGMA(X)
+#undef X
+            default: e = hipErrorInvalidValue;
+        }
+    }
+    if (e != hipSuccess) return CSR5_EHIP;
+    h->in_csr5_order = false;
+    return CSR5_OK;
+}
+
+int csr5_free(csr5_handle_t h) {
+    if (!h) return CSR5_OK;
+    int rc = CSR5_OK;
+    if (h->owned && hipFree(h->owned) != hipSuccess) rc = CSR5_EHIP;
+    delete h;
+    return rc;
+}
+
+int csr5_status(csr5_handle_t h, uint32_t* status) {
+    if (!h || !status) return CSR5_EINVAL;
+    if (hipMemcpyAsync(status, h->status, 4, hipMemcpyDeviceToHost, h->conv_stream) != hipSuccess) return CSR5_EHIP;
+    if (hipStreamSynchronize(h->conv_stream) != hipSuccess) return CSR5_EHIP;
+    return CSR5_OK;
+}
+
+int csr5_get_info(csr5_handle_t h, int32_t* omega, int32_t* sigma, int32_t* p, int32_t* p_complete,
+                  int32_t* desc_words_per_lane, int32_t* empty_offset_len) {
+    if (!h) return CSR5_EINVAL;
+    if (omega) *omega = OMEGA;
+    if (sigma) *sigma = h->g.sigma;
+    if (p) *p = h->g.p;
+    if (p_complete) *p_complete = h->g.pc;
+    if (desc_words_per_lane) *desc_words_per_lane = h->g.W;
+    if (empty_offset_len) {
+        int32_t v = 0;
+        if (hipMemcpyAsync(&v, h->eop + h->g.pc, 4, hipMemcpyDeviceToHost, h->conv_stream) != hipSuccess) return CSR5_EHIP;
+        if (hipStreamSynchronize(h->conv_stream) != hipSuccess) return CSR5_EHIP;
+        *empty_offset_len = v;
+    }
+    return CSR5_OK;
+}
+
+int csr5_get_arrays(csr5_handle_t h, const uint32_t** tile_ptr, const uint32_t** tile_desc,
+                    const int32_t** empty_offset_ptr, const int32_t** empty_offset) {
+    if (!h) return CSR5_EINVAL;
+    if (tile_ptr) *tile_ptr = h->tile_ptr;
+    if (tile_desc) *tile_desc = h->tile_desc;
+    if (empty_offset_ptr) *empty_offset_ptr = h->eop;
+    if (empty_offset) *empty_offset = h->eo;
+    return CSR5_OK;
+}
+
+int csr5_read_array(csr5_handle_t h, int which, void* dst_host, size_t bytes) {
+    if (!h || (!dst_host && bytes)) return CSR5_EINVAL;
+    const void* src = nullptr;
+    size_t have = 0;
+    switch (which) {
+        case CSR5_ARRAY_TILE_PTR: src = h->tile_ptr; have = (size_t(h->g.p) + 1) * 4; break;
+        case CSR5_ARRAY_TILE_DESC: src = h->tile_desc; have = size_t(h->g.pc) * h->g.W * OMEGA * 4; break;
+        case CSR5_ARRAY_EMPTY_OFFSET_PTR: src = h->eop; have = (size_t(h->g.pc) + 1) * 4; break;
+        case CSR5_ARRAY_EMPTY_OFFSET: {
+            int32_t len = 0;
+            int rc = csr5_get_info(h, nullptr, nullptr, nullptr, nullptr, nullptr, &len);
+            if (rc != CSR5_OK) return rc;
+            src = h->eo; have = size_t(len) * 4;
+            break;
+        }
+        default: return CSR5_EINVAL;
+    }
+    if (bytes > have) return CSR5_EINVAL;
+    if (bytes == 0) return CSR5_OK;
+    if (hipMemcpyAsync(dst_host, src, bytes, hipMemcpyDeviceToHost, h->conv_stream) != hipSuccess) return CSR5_EHIP;
+    if (hipStreamSynchronize(h->conv_stream) != hipSuccess) return CSR5_EHIP;
+    return CSR5_OK;
+}
+
+}  // extern "C"

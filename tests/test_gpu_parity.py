@@ -1,0 +1,156 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle.
+Format arrays bit-exact; y within 1e-12 * sum_j|a_ij x_j| + 1e-300 per row."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1503_05032_amd import binding as B
+from paper_1503_05032_amd import workloads as wl
+
+from gpu_util import DeviceCsr, check_format, check_spmv, convert
+
+pytestmark = pytest.mark.gpu
+
+SIGMAS_EDGE = [1, 4, 7, 16, 20, 32, 33, 46, 48]
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.mark.parametrize("sigma", SIGMAS_EDGE)
+def test_edge_cases(sigma):
+    T = 64 * sigma
+    for a in wl.edge_cases(T):
+        say("edge", sigma, a.name, a.m, a.n, a.nnz)
+        d = DeviceCsr(a)
+        h = convert(d, sigma=sigma)
+        check_format(d, h, (a.name, sigma))
+        check_spmv(d, h, (a.name, sigma))
+        B.csr5_to_csr(h)
+        torch.cuda.synchronize()
+        if a.nnz:
+            assert np.array_equal(d.col_idx.cpu().numpy(), a.col_idx), (a.name, "to_csr col")
+            assert np.array_equal(d.val.cpu().numpy(), a.val), (a.name, "to_csr val")
+        B.csr5_free(h)
+
+
+@pytest.mark.parametrize("sigma", list(range(1, 49)))
+def test_every_sigma_small(sigma):
+    a = wl.tiny_uniform(m=1500, n=1200, max_len=25, seed=sigma)
+    say("sigma", sigma, a.nnz)
+    d = DeviceCsr(a)
+    h = convert(d, sigma=sigma)
+    check_format(d, h, ("tiny", sigma))
+    check_spmv(d, h, ("tiny", sigma))
+    B.csr5_free(h)
+
+
+def test_config1_auto_sigma_and_plain_convert():
+    a = wl.config(1)
+    d = DeviceCsr(a)
+    say("config1 via csr5_convert", a.stats())
+    h = B.csr5_convert(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val)     # hipMalloc path, auto sigma
+    info = B.csr5_get_info(h)
+    assert info["sigma"] == B.csr5_sigma_auto(a.nnz, a.m)
+    check_format(d, h, "config1")
+    check_spmv(d, h, "config1")
+    # a second x through the same handle, and the non-_ex entry point
+    x2 = np.random.default_rng(9).uniform(-1, 1, size=a.n)
+    check_spmv(d, h, "config1-x2", x=x2)
+    d.y.fill_(float("nan"))
+    B.csr5_spmv(h, d.x, d.y)
+    torch.cuda.synchronize()
+    y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, x2)
+    assert np.all(np.abs(d.y.cpu().numpy() - y_ref) <= 1e-12 * s + 1e-300)
+    B.csr5_free(h)
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_configs(cfg):
+    say("generating config", cfg)
+    a = wl.config(cfg)
+    say(a.stats())
+    d = DeviceCsr(a)
+    h = convert(d, sigma=0)
+    say("converted; sigma", B.csr5_get_info(h)["sigma"])
+    check_format(d, h, f"config{cfg}")
+    say("format ok")
+    worst = check_spmv(d, h, f"config{cfg}")
+    say("spmv ok, worst err/sum|ax| =", worst)
+    B.csr5_free(h)
+
+
+def test_workspace_and_malloc_paths_agree():
+    a = wl.config(3, scale=0.02)
+    d1, d2 = DeviceCsr(a), DeviceCsr(a)
+    h1 = convert(d1, sigma=12, use_workspace=True, flags=B.CSR5_FLAG_NO_HOST_CHECK)
+    h2 = convert(d2, sigma=12, use_workspace=False)
+    for which in range(4):
+        assert np.array_equal(B.csr5_read_array(h1, which), B.csr5_read_array(h2, which))
+    check_format(d1, h1, "ws")
+    check_spmv(d1, h1, "ws")
+    check_spmv(d2, h2, "malloc")
+    B.csr5_free(h1)
+    B.csr5_free(h2)
+
+
+def test_error_paths():
+    a = wl.tiny_uniform(m=300, n=300, seed=1)
+    d = DeviceCsr(a)
+    rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val, sigma=49, check=False)
+    assert rc == B.CSR5_ERANGE and not h
+    rc, h = B.csr5_convert_ex(-1, a.n, a.nnz, d.row_ptr, d.col_idx, d.val, check=False)
+    assert rc == B.CSR5_EINVAL and not h
+    rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz, None, d.col_idx, d.val, check=False)
+    assert rc == B.CSR5_EINVAL and not h
+    rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr, None, d.val, check=False)
+    assert rc == B.CSR5_EINVAL and not h
+    # nnz that does not match row_ptr[m]: caught by the host check
+    rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz - 1, d.row_ptr, d.col_idx, d.val, check=False)
+    assert rc == B.CSR5_EINVAL and not h
+    # workspace too small
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val, sigma=4, workspace=ws, check=False)
+    assert rc == B.CSR5_ENOMEM and not h
+    assert B.csr5_spmv(None, d.x, d.y, check=False) == B.CSR5_EINVAL
+    assert B.csr5_free(None) == B.CSR5_OK
+    # decreasing row_ptr in the middle: device-side validation reports it, spmv leaves y alone
+    rp = a.row_ptr.copy()
+    rp[100], rp[101] = rp[101] + 3, rp[100]
+    d2 = DeviceCsr(a)
+    d2.row_ptr = torch.from_numpy(rp).to("cuda:0")
+    h = B.csr5_convert_ex(a.m, a.n, a.nnz, d2.row_ptr, d2.col_idx, d2.val, sigma=4)
+    assert B.csr5_status(h) & B.CSR5_STATUS_BAD_ROW_PTR
+    B.csr5_free(h)
+    # a column index out of range
+    ci = a.col_idx.copy()
+    ci[77] = a.n + 5
+    d3 = DeviceCsr(a)
+    d3.col_idx = torch.from_numpy(ci).to("cuda:0")
+    h = B.csr5_convert_ex(a.m, a.n, a.nnz, d3.row_ptr, d3.col_idx, d3.val, sigma=4)
+    assert B.csr5_status(h) & B.CSR5_STATUS_BAD_COL_IDX
+    d3.y.fill_(123.0)
+    B.csr5_spmv(h, d3.x, d3.y)
+    torch.cuda.synchronize()
+    yy = d3.y.cpu().numpy()
+    assert np.all((yy == 0.0) | (yy == 123.0))      # zero-filled at most; nothing gathered
+    B.csr5_free(h)
+
+
+def test_repeatability_within_tolerance():
+    a = wl.config(4, scale=0.02)
+    d = DeviceCsr(a)
+    h = convert(d, sigma=0)
+    ys = []
+    for _ in range(3):
+        check_spmv(d, h, "repeat")
+        ys.append(d.y.cpu().numpy().copy())
+    _, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
+    assert np.all(np.abs(ys[0] - ys[1]) <= 2e-12 * s + 1e-300)
+    assert np.all(np.abs(ys[0] - ys[2]) <= 2e-12 * s + 1e-300)
+    B.csr5_free(h)
