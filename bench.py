@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of libcsr5 on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--sigma 0]
+
+One "step" is one y = A*x on the CSR5 form of the workload (the tile kernel plus
+the carry fix-up kernel, i.e. one csr5_spmv call) with every input resident in HBM.
+The CSR -> CSR5 conversion is timed in the same run and reported in units of one
+SpMV.  Prints ONE JSON line.  The headline value is SpMV GFLOP/s = 2*nnz / t.
+
+The CPU oracle is used for two things only: a correctness check of the timed
+configuration, and the `cpu_baseline` figure (the oracle timed as it stands on
+one host core).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def bytes_model(a, info, n_ref):
+    """Algorithmic bytes of one SpMV: val + col_idx (12 B per nonzero), packed
+    descriptors, tile_ptr, empty_offset and its per-tile starts, every
+    referenced x entry once, y written once."""
+    W, p, pc, E = info["desc_words_per_lane"], info["p"], info["p_complete"], info["empty_offset_len"]
+    return (12 * a.nnz + 4 * W * 64 * pc + 4 * (p + 1) + 4 * (pc + 1) + 4 * E + 8 * n_ref + 8 * a.m)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: the 27-point stencil)")
+    ap.add_argument("--sigma", type=int, default=0, help="tile height, 0 = the library's rule")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--quick", action="store_true", help="skip the conversion/cold/batch extras")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the method has no multi-GPU part); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1503_05032_amd import binding as B
+    from paper_1503_05032_amd import build as libbuild
+    from paper_1503_05032_amd import workloads as wl
+
+    if not os.path.exists(B.LIB_PATH):
+        libbuild.build(verbose=False)
+    B.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+
+    a = wl.config(args.workload)
+    st = a.stats()
+    n_ref = int(np.unique(a.col_idx).size)
+    row_ptr = torch.from_numpy(a.row_ptr).to(dev)
+    col0 = torch.from_numpy(a.col_idx).to(dev)        # pristine CSR copies
+    val0 = torch.from_numpy(a.val).to(dev)
+    col = col0.clone()
+    val = val0.clone()
+    x = torch.from_numpy(a.x).to(dev)
+    y = torch.empty(a.m, dtype=torch.float64, device=dev)
+
+    sigma = args.sigma or B.csr5_sigma_auto(a.nnz, a.m)
+    ws = torch.empty(B.csr5_workspace_bytes(a.m, a.nnz, sigma), dtype=torch.uint8, device=dev)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    # ---------------------------------------------------------------- conversion
+    conv_ms, conv_alloc_ms = [], []
+    h = None
+    nconv = 1 if args.quick else 7
+    for it in range(nconv):
+        if h is not None:
+            B.csr5_free(h)
+        col.copy_(col0)
+        val.copy_(val0)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        h = B.csr5_convert_ex(a.m, a.n, a.nnz, row_ptr, col, val, sigma=sigma, workspace=ws,
+                              flags=B.CSR5_FLAG_NO_HOST_CHECK)
+        e1.record()
+        torch.cuda.synchronize()
+        conv_ms.append(e0.elapsed_time(e1))
+    if not args.quick:
+        for it in range(5):           # the plain entry point: hipMalloc + host check inside
+            c2, v2 = col0.clone(), val0.clone()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            h2 = B.csr5_convert_ex(a.m, a.n, a.nnz, row_ptr, c2, v2, sigma=sigma)
+            torch.cuda.synchronize()
+            conv_alloc_ms.append((time.perf_counter() - t0) * 1e3)
+            B.csr5_free(h2)
+            del c2, v2
+    status = B.csr5_status(h)
+    info = B.csr5_get_info(h)
+    assert status & 3 == 0, status
+
+    # ---------------------------------------------------------------- correctness of this configuration
+    import oracle
+    B.csr5_spmv_ex(h, x, y)
+    torch.cuda.synchronize()
+    y_ref, s_abs = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
+    err = np.abs(y.cpu().numpy() - y_ref)
+    parity_ok = bool(np.all(err <= 1e-12 * s_abs + 1e-300))
+
+    # ---------------------------------------------------------------- timed region: exactly K steps
+    for _ in range(args.warmup):
+        B.csr5_spmv_ex(h, x, y)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(args.steps):
+        B.csr5_spmv_ex(h, x, y)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    gflops = 2.0 * a.nnz / (ms_per_step * 1e-3) / 1e9
+    B_model = bytes_model(a, info, n_ref)
+    B_gather = B_model - 8 * n_ref + 8 * a.nnz
+
+    extras = {}
+    if not args.quick:
+        # the paper's protocol (Section 5.1) scaled down: best of 10 batches of 100 runs
+        best = 1e30
+        for _ in range(10):
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(100):
+                B.csr5_spmv_ex(h, x, y)
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) / 100)
+        extras["ms_best_of_10x100"] = round(best, 5)
+        # cache-cold: stream 1 GiB through the caches before every launch
+        flush = torch.empty(1 << 27, dtype=torch.float64, device=dev)
+        cold = []
+        for _ in range(10):
+            flush.add_(1.0)
+            e0, e1 = ev(), ev()
+            e0.record()
+            B.csr5_spmv_ex(h, x, y)
+            e1.record()
+            torch.cuda.synchronize()
+            cold.append(e0.elapsed_time(e1))
+        del flush
+        extras["ms_cold_median"] = round(float(np.median(cold)), 5)
+
+    # ---------------------------------------------------------------- dominant kernel, HIP events inside the library
+    ms_tiles, ms_fixup = B.csr5_spmv_profile(h, x, y, reps=min(max(args.steps, 50), 2000))
+    achieved = B_model / (ms_tiles * 1e-3) / 1e9
+
+    conv = float(np.median(conv_ms))
+    out = {
+        "metric": "SpMV GFLOP/s & achieved HBM GB/s (% of peak), fp64; convert time in SpMVs",
+        "value": round(gflops, 2),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {
+            "workload": f"configs[{args.workload - 1}] {a.name}: {a.m}x{a.n}, nnz={a.nnz}, "
+                        f"nnz/row min/avg/max={st['row_len_min']}/{st['row_len_avg']:.2f}/{st['row_len_max']}, "
+                        f"empty rows={st['empty_rows']}",
+            "omega": 64, "sigma": info["sigma"], "tiles": info["p"],
+            "desc_words_per_lane": info["desc_words_per_lane"],
+            "empty_offset_len": info["empty_offset_len"],
+        },
+        "parity_ok": parity_ok,
+        "spmv": {
+            "gflops": round(gflops, 2),
+            "bytes_model": B_model,
+            "gbs_model": round(B_model / (ms_per_step * 1e-3) / 1e9, 1),
+            "pct_hbm_peak_model": round(100 * B_model / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+            "gbs_if_every_gather_missed": round(B_gather / (ms_per_step * 1e-3) / 1e9, 1),
+            "wall_ms_per_step": round(wall_ms / args.steps, 5),
+            **extras,
+        },
+        "convert": {
+            "ms_workspace_no_host_check": round(conv, 4),
+            "in_spmvs": round(conv / ms_per_step, 2),
+            "ms_with_hipmalloc_and_host_check": round(float(np.median(conv_alloc_ms)), 4) if conv_alloc_ms else None,
+            "in_spmvs_with_hipmalloc": round(float(np.median(conv_alloc_ms)) / ms_per_step, 2) if conv_alloc_ms else None,
+        },
+        "roofline": {
+            "kernel": f"k_spmv<{info['sigma']}>",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": MEASURED_TRAFFIC.get((args.workload, info["sigma"])),
+            "kernel_ms": round(ms_tiles, 5),
+            "fixup_kernel_ms": round(ms_fixup, 5),
+            "bytes_per_launch": B_model,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        # the oracle as it stands (sequential Algorithm 1, one core), repeated on the
+        # same matrix until about cpu_seconds of work
+        reps, t_acc = 0, 0.0
+        while t_acc < args.cpu_seconds and reps < 2000:
+            t0 = time.perf_counter()
+            oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
+            t_acc += time.perf_counter() - t0
+            reps += 1
+        out["cpu_baseline"] = {
+            "value": round(2.0 * a.nnz * reps / t_acc / 1e9, 3),
+            "unit": "GFLOP/s",
+            "cores": 1,
+            "kind": "oracle",
+            "sample": f"{reps} full SpMVs of the same matrix (sequential Algorithm 1, gcc -O2), "
+                      f"{t_acc:.1f} s of CPU time; host has {os.cpu_count()} logical CPUs",
+        }
+
+    B.csr5_free(h)
+    print(json.dumps(out))
+
+
+# HBM traffic of one tile-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# keyed by (workload, sigma); the profiles/ folder holds the runs these come from.
+MEASURED_TRAFFIC: dict = {}
+
+
+if __name__ == "__main__":
+    main()

@@ -50,6 +50,7 @@ enum {
 #define CSR5_STATUS_BAD_ROW_PTR 1u /* row_ptr decreasing or outside [0, nnz] */
 #define CSR5_STATUS_BAD_COL_IDX 2u /* a column index outside [0, n) */
 #define CSR5_STATUS_HAS_DIRTY 4u   /* informational: some tile holds an empty row */
+#define CSR5_STATUS_HAS_EMPTY_ROWS 8u /* informational: the matrix has a row without nonzeros */
 
 /*
  * sigma from nnz/row (Section 3.2): the paper's four-way rule with bounds
@@ -63,7 +64,8 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * nnz nonzeros at the given sigma (0 = the value csr5_sigma_auto picks).  An
  * upper bound computable on the host: tile_ptr (p+1 words) + tile_desc
  * (p_c*W*64 words) + empty_offset_ptr (p_c+1 words) + empty_offset (at most
- * min(m + p_c, p_c*T) words) + a status word, each rounded up to 256 bytes.
+ * min(m + p_c, p_c*T) words) + the SpMV's auxiliary array (p+1 doubles) + a
+ * status word, each rounded up to 256 bytes.
  * Returns 0 for invalid arguments.
  */
 size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma);
@@ -102,15 +104,27 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, i
                     void *hip_stream, uint32_t flags, csr5_handle_t *out);
 
 /*
- * y = A*x (Section 4: Algorithm 8 per complete tile, the tile's first and last
- * segment added atomically, the entries after the last complete tile by a
- * row-wise SIMD reduction).  x double[n], y double[m]; y is overwritten (rows
- * without nonzeros get 0).  x and y must not overlap.  Asynchronous.
- * Summation order differs from CSR order and, through the atomics, may differ
- * between runs in the last bits.
+ * y = A*x (Section 4: Algorithm 8 per complete tile; a tile's first segment,
+ * when it continues a row of an earlier tile, goes through an auxiliary array
+ * that a second small kernel adds to y; the entries after the last complete
+ * tile by a row-wise SIMD reduction).  x double[n], y double[m]; y is
+ * overwritten (rows without nonzeros get 0).  x and y must not overlap.
+ * Asynchronous.  Summation order differs from CSR order.  The auxiliary array
+ * lives in the handle: calls on ONE handle must not overlap in time (use one
+ * stream, or order them).
  */
 int csr5_spmv(csr5_handle_t h, const double *x, double *y);
 int csr5_spmv_ex(csr5_handle_t h, const double *x, double *y, void *hip_stream);
+
+/*
+ * Measurement helper: runs the SpMV `reps` times on the stream with HIP events
+ * recorded around each of its kernels, waits, and returns the mean duration of
+ * each in milliseconds: ms[0] the tile kernel (all complete tiles plus the
+ * workgroup for the incomplete one), ms[1] the carry fix-up.  ms is a host
+ * array of 2 floats.  y ends up holding A*x as after csr5_spmv.
+ */
+int csr5_spmv_profile(csr5_handle_t h, const double *x, double *y, void *hip_stream, int reps,
+                      float *ms);
 
 /*
  * CSR5 -> CSR (Section 3.6): transposes col_idx and val of every complete tile

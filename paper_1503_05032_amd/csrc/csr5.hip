@@ -81,6 +81,11 @@ __device__ __forceinline__ int count_le_tileptr(const uint32_t* a, int len, uint
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (OMEGA - 1); }
 
+// Native global fp64 atomic add, no return value.
+__device__ __forceinline__ void atomic_add_f64(double* addr, double v) {
+    __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Workgroups are dealt round-robin to the 8 XCDs.  Give every XCD one
 // contiguous range of logical blocks instead, so that neighbouring tiles (which
 // gather neighbouring parts of x) share one L2 rather than eight.
@@ -131,6 +136,8 @@ k_rows(int m, int nnz, const int32_t* __restrict__ row_ptr, int sigma, int T, in
         return;
     }
     if (a == b) {
+        // one flag write per wavefront is enough: the lowest lane that sees an empty row
+        if (lane_id() == __builtin_ctzll(__ballot(1))) atomicOr(status, CSR5_STATUS_HAS_EMPTY_ROWS);
         int t = count_le_tileptr(tile_ptr, p + 1, uint32_t(r)) - 1;
         if (t >= 0 && t < p) {
             uint32_t old = atomicOr(&tile_ptr[t], DIRTY);
@@ -302,6 +309,14 @@ struct TransposeShape {
     static constexpr int PITCH = SIGMA | 1;
 };
 
+// Orders LDS traffic between the lanes of ONE wavefront: LDS instructions of a
+// wavefront execute in order, so what is needed is that the compiler keeps the
+// stores before and the loads after this point.
+__device__ __forceinline__ void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 template <int SIGMA, bool BACK>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
 k_transpose(int pc, int n, int nnz, int32_t* __restrict__ col_idx, double* __restrict__ val,
@@ -394,26 +409,6 @@ k_transpose(int pc, int n, int nnz, int32_t* __restrict__ col_idx, double* __res
 }
 
 // ----------------------------------------------------------------------------
-// y <- 0.  The tiles add their first and last segment atomically (Section 4),
-// and rows without nonzeros are never stored by any tile, so y starts at zero.
-// A fill kernel rather than a memset node, so that callers may capture
-// csr5_spmv into a HIP graph.
-// ----------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_zero_f64(double* __restrict__ y, size_t m) {
-    size_t gid = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    size_t stride = size_t(gridDim.x) * blockDim.x;
-    // two doubles per store where alignment allows
-    size_t m2 = m / 2;
-    if ((reinterpret_cast<uintptr_t>(y) & 15) == 0) {
-        double2* y2 = reinterpret_cast<double2*>(y);
-        for (size_t k = gid; k < m2; k += stride) y2[k] = make_double2(0.0, 0.0);
-        if (gid == 0 && (m & 1)) y[m - 1] = 0.0;
-    } else {
-        for (size_t k = gid; k < m; k += stride) y[k] = 0.0;
-    }
-}
-
-// ----------------------------------------------------------------------------
 // CSR5 SpMV (Algorithm 8), one wavefront per complete tile, lane i = column i.
 //
 // Lane i streams its sigma (val, col_idx) pairs -- at each step j the 64 lanes
@@ -432,40 +427,56 @@ __global__ void __launch_bounds__(256) k_zero_f64(double* __restrict__ y, size_t
 // column i is exactly tmp[i .. i+seg_offset[i]], the value Algorithm 6 defines;
 // seg_offset itself is not read (the ballot carries the same information).
 //
-// Cross-tile (Section 4): segment 0 of a tile may continue a row opened by the
-// previous tile and the last segment may be continued by the next one; both are
-// added with a hardware fp64 atomic onto the zeroed y.  All other segments are
-// owned by this tile and are plain stores.
+// Cross-tile (Section 4 offers atomic adds or a global auxiliary array; device
+// wide fp64 atomics are resolved on the memory side of the eight L2s on this
+// chip and, at two per tile, measured slower than everything else in the kernel
+// together, so the auxiliary array it is).  Only segment 0 of a tile can
+// continue a row that an earlier tile opened (it does iff the tile's first
+// nonzero is not its row's first: row_ptr[tile_ptr] != tile*T).  Such a
+// continuation goes to carry[tile]; every other segment, including the tile's
+// last, is a plain store: the tile holds that row's first nonzero, so it writes
+// the row's base value, and k_spmv_fixup adds the carries afterwards.  y needs
+// no zero-fill and the result does not depend on scheduling.
 //
-// The extra last workgroup handles the entries after the last complete tile.
+// Workgroup 0 handles the entries after the last complete tile when there are
+// any (early, so that its dependent searches hide behind the tiles).
 // ----------------------------------------------------------------------------
 template <int SIGMA>
 struct FlagWord {
     using type = typename std::conditional<(SIGMA > 32), uint64_t, uint32_t>::type;
 };
 
-__device__ __forceinline__ void atomic_add_f64(double* addr, double v) {
-    // gfx950 has a native global fp64 atomic add; no return value needed
-    __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+constexpr int TAIL_MAX_CHUNKS = (CSR5_SIGMA_MAX * OMEGA) / OMEGA + 1;   // 64-entry chunks in < one tile
 
-__device__ void spmv_tail(int m, int nnz, int64_t first_entry, uint32_t tile_ptr_last,
+// Entries after the last complete tile (Section 4, last paragraph: a CSR-vector
+// style pass).  64 consecutive entries per wavefront step; the row of each entry
+// comes from a binary search (so runs of empty rows cost nothing); a shuffle
+// scan sums runs of equal row.  A row that lies inside one 64-entry chunk is
+// stored directly.  A row cut by a chunk boundary is accumulated in LDS, in the
+// slot of the chunk it starts in (at most one row starts in a chunk and leaves
+// it), and stored at the end.  The part of a row that began in the complete
+// tiles goes to carry[pc] like a tile's segment 0.
+__device__ void spmv_tail(int m, int nnz, int first, uint32_t tile_ptr_last,
                           const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                           const double* __restrict__ val, const double* __restrict__ x,
-                          double* __restrict__ y) {
-    // CSR-vector in spirit (Section 4, last paragraph): 64 consecutive entries
-    // per wavefront, a shuffle reduction over runs of equal row, one atomic per
-    // run (the first row may be shared with the last complete tile).  Rows are
-    // found per entry by binary search so that trailing empty rows cost nothing.
-    int lane = lane_id();
+                          double* __restrict__ y, double* __restrict__ carry_slot) {
+    __shared__ double acc[TAIL_MAX_CHUNKS];
+    __shared__ int acc_row[TAIL_MAX_CHUNKS];
+    __shared__ double acc_first;
+    const int lane = lane_id();
+    const int wave = threadIdx.x / OMEGA, nwaves = blockDim.x / OMEGA;
+    for (int q = threadIdx.x; q < TAIL_MAX_CHUNKS; q += blockDim.x) { acc[q] = 0.0; acc_row[q] = -1; }
+    if (threadIdx.x == 0) acc_first = 0.0;
+    __syncthreads();
     int row_lo = int(tile_ptr_last & ROWMASK);
     if (row_lo > m) row_lo = m;
-    int64_t span = int64_t(nnz) - first_entry;
-    int64_t rounds = (span + blockDim.x - 1) / blockDim.x;
-    for (int64_t it = 0; it < rounds; it++) {
-        int64_t e = first_entry + it * blockDim.x + threadIdx.x;
-        bool live = e < int64_t(nnz);
-        int row = -1;
+    const int span = nnz - first;
+    const int nchunks = (span + OMEGA - 1) / OMEGA;
+    for (int q = wave; q < nchunks && q < TAIL_MAX_CHUNKS; q += nwaves) {
+        const int chunk_lo = first + q * OMEGA;
+        const int e = chunk_lo + lane;
+        const bool live = e < nnz;
+        int row = -2 - lane;                         // distinct keys for dead lanes
         double prod = 0.0;
         if (live) {
             row = row_lo + count_le_i32(row_ptr + row_lo, m + 1 - row_lo, e) - 1;
@@ -478,41 +489,70 @@ __device__ void spmv_tail(int m, int nnz, int64_t first_entry, uint32_t tile_ptr
             if (lane >= d && rup == row) prod += up;
         }
         int rnext = __shfl_down(row, 1, OMEGA);
-        bool last_of_run = (lane == OMEGA - 1) || (rnext != row);
-        if (live && last_of_run && row >= 0 && row < m) atomic_add_f64(&y[row], prod);
+        bool run_end = live && ((lane == OMEGA - 1) || (rnext != row));
+        if (run_end && row >= 0 && row < m) {
+            int rs = row_ptr[row], re = row_ptr[row + 1];
+            if (rs >= chunk_lo && re <= chunk_lo + OMEGA) {
+                y[row] = prod;                       // the whole row lies in this chunk
+            } else if (rs < first) {
+                atomicAdd(&acc_first, prod);         // continues a row of the complete tiles
+            } else {
+                int q1 = (rs - first) / OMEGA;       // chunk the row starts in
+                if (q1 >= 0 && q1 < TAIL_MAX_CHUNKS) {
+                    atomicAdd(&acc[q1], prod);
+                    acc_row[q1] = row;
+                }
+            }
+        }
     }
+    __syncthreads();
+    for (int q = threadIdx.x; q < TAIL_MAX_CHUNKS; q += blockDim.x)
+        if (acc_row[q] >= 0) y[acc_row[q]] = acc[q];
+    if (threadIdx.x == 0) *carry_slot = acc_first;
 }
 
 template <int SIGMA>
-__global__ void __launch_bounds__(256)
-k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, const int32_t* __restrict__ row_ptr,
-       const uint32_t* __restrict__ tile_ptr, const uint32_t* __restrict__ tile_desc,
-       const int32_t* __restrict__ eop, const int32_t* __restrict__ eo,
-       const int32_t* __restrict__ col_idx, const double* __restrict__ val,
-       const double* __restrict__ x, double* __restrict__ y, const uint32_t* __restrict__ status) {
+__global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
+k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
+       const int32_t* __restrict__ row_ptr, const uint32_t* __restrict__ tile_ptr,
+       const uint32_t* __restrict__ tile_desc, const int32_t* __restrict__ eop,
+       const int32_t* __restrict__ eo, const int32_t* __restrict__ col_idx,
+       const double* __restrict__ val, const double* __restrict__ x, double* __restrict__ y,
+       double* __restrict__ carry, const uint32_t* __restrict__ status) {
     constexpr int T = OMEGA * SIGMA;
     constexpr int YBITS = 32 - __builtin_clz(uint32_t(T - 1));        // ceil(log2(64*sigma))
     constexpr int W = (SIGMA + SBITS + YBITS + 31) / 32;
     constexpr int YSH = SIGMA + SBITS;
-    constexpr int WAVES = 4;
+    constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
+    constexpr int PITCH = TransposeShape<SIGMA>::PITCH;
     using flag_t = typename FlagWord<SIGMA>::type;
+    __shared__ double lds[WAVES][OMEGA * PITCH];
 
     const uint32_t st = *status;      // consulted below, after the streaming loads are in flight
 
-    if (blockIdx.x >= nb_tiles) {     // the one extra workgroup: incomplete last tile
+    if (blockIdx.x < has_tail) {      // workgroup 0: incomplete last tile
         if (st & BAD_BITS) return;
-        spmv_tail(m, nnz, int64_t(pc) * T, tile_ptr[pc], row_ptr, col_idx, val, x, y);
+        spmv_tail(m, nnz, pc * T, tile_ptr[pc], row_ptr, col_idx, val, x, y, carry + pc);
         return;
     }
-    int lane = lane_id();
-    int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / OMEGA);
-    int tile = int(xcd_remap(blockIdx.x, nb_tiles)) * WAVES + wave;
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / OMEGA);
+    const int tile = int(xcd_remap(blockIdx.x - has_tail, nb_tiles)) * WAVES + wave;
     if (tile >= pc) return;
 
+    // ---- stream the tile: at step j the 64 lanes read 64 consecutive entries
+    const size_t base = size_t(tile) * T + lane;
+    int32_t c[SIGMA];
+    double v[SIGMA];
+#pragma unroll
+    for (int j = 0; j < SIGMA; j++) c[j] = __builtin_nontemporal_load(&col_idx[base + j * OMEGA]);
+#pragma unroll
+    for (int j = 0; j < SIGMA; j++) v[j] = __builtin_nontemporal_load(&val[base + j * OMEGA]);
+
     // ---- descriptor
-    uint32_t tp = tile_ptr[tile];
-    bool dirty = (tp & DIRTY) != 0;
-    uint32_t row0 = tp & ROWMASK;
+    const uint32_t tp = tile_ptr[tile];
+    const bool dirty = (tp & DIRTY) != 0;
+    const uint32_t row0 = tp & ROWMASK;
     const uint32_t* dp = tile_desc + size_t(tile) * W * OMEGA + lane;
     uint64_t lo = __builtin_nontemporal_load(dp);
     if (W > 1) lo |= uint64_t(__builtin_nontemporal_load(dp + OMEGA)) << 32;
@@ -520,7 +560,7 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, const int32_t* __restrict__ ro
     if (W > 2) hi = __builtin_nontemporal_load(dp + 2 * OMEGA);
     constexpr int FLAG_BITS = 8 * int(sizeof(flag_t));
     constexpr flag_t FLAG_MASK = (SIGMA == FLAG_BITS) ? ~flag_t(0) : flag_t((flag_t(1) << (SIGMA % FLAG_BITS)) - 1);
-    flag_t flags = flag_t(lo) & FLAG_MASK;
+    const flag_t flags = flag_t(lo) & FLAG_MASK;
     uint32_t yo = uint32_t(lo >> YSH);
     if (W > 2) yo |= uint32_t(hi << (64 - YSH));
     // empty_offset slice of a tile that holds empty rows (Algorithm 8 line 4)
@@ -531,25 +571,61 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, const int32_t* __restrict__ ro
         eo_t = eo + e0;
         nseg_t = uint32_t(e1 - e0);
     }
+    if ((st & BAD_BITS) || row0 >= uint32_t(m)) return;   // rejected input: gather and store nothing
+    // does segment 0 continue a row that an earlier tile opened?
+    const bool cont0 = row_ptr[row0] != tile * T;
 
-    // ---- stream the tile and gather x
-    const size_t base = size_t(tile) * T + lane;
-    int32_t c[SIGMA];
-    double v[SIGMA];
-#pragma unroll
-    for (int j = 0; j < SIGMA; j++) c[j] = __builtin_nontemporal_load(&col_idx[base + j * OMEGA]);
-#pragma unroll
-    for (int j = 0; j < SIGMA; j++) v[j] = __builtin_nontemporal_load(&val[base + j * OMEGA]);
-    if (st & BAD_BITS) return;        // conversion rejected the input: gather and store nothing
+    // ---- gather x.  Lane i owns the CSR entries i*sigma .. i*sigma+sigma-1 of the
+    // tile, so at a fixed step the 64 lanes would gather from 64 unrelated
+    // places.  Consecutive CSR entries, however, have increasing and often
+    // adjacent columns.  So the column indices take a round trip through LDS:
+    // written by their owners, read back so that lane L holds CSR entries
+    // k*64+L (64 consecutive entries per gather instruction: few distinct cache
+    // lines), x is gathered in that order, and the values return through the
+    // same LDS buffer to the owners.  Rows are padded to an odd pitch.
     double xv[SIGMA];
+#ifdef CSR5_EXP_DIRECT_GATHER
 #pragma unroll
     for (int j = 0; j < SIGMA; j++) xv[j] = x[c[j]];
+#else
+    {
+        double* xb = lds[wave];
+        int32_t* cb = reinterpret_cast<int32_t*>(xb);
+#pragma unroll
+        for (int j = 0; j < SIGMA; j++) cb[lane * PITCH + j] = c[j];
+        wave_sync_lds();
+#pragma unroll
+        for (int k = 0; k < SIGMA; k++) {
+            const int e = k * OMEGA + lane;
+            c[k] = cb[(e / SIGMA) * PITCH + (e % SIGMA)];
+        }
+        wave_sync_lds();
+#pragma unroll
+        for (int k = 0; k < SIGMA; k++) xv[k] = x[c[k]];
+#pragma unroll
+        for (int k = 0; k < SIGMA; k++) {
+            const int e = k * OMEGA + lane;
+            xb[(e / SIGMA) * PITCH + (e % SIGMA)] = xv[k];
+        }
+        wave_sync_lds();
+#pragma unroll
+        for (int j = 0; j < SIGMA; j++) xv[j] = xb[lane * PITCH + j];
+    }
+#endif
 
-    // Row of segment number s of this tile.  The bound checks cannot fail for a
-    // consistent descriptor; they keep a corrupted one from writing outside y.
-    auto seg_row = [&](uint32_t s) -> uint32_t {
-        if (!dirty) return row0 + s;
-        return s < nseg_t ? row0 + uint32_t(eo_t[s]) : uint32_t(m);
+    // Store the finished sum of segment number s of this tile.  The bound checks
+    // cannot fail for a consistent descriptor; they keep a corrupted one from
+    // writing outside y.  Only lane 0 ever closes segment 0 (every other column
+    // has the forced first flag before it, so its y_offset is >= 1).
+    auto put = [&](uint32_t s, double value) {
+        uint32_t row;
+        if (!dirty) row = row0 + s;
+        else row = s < nseg_t ? row0 + uint32_t(eo_t[s]) : uint32_t(m);
+        if (s == 0) {
+            carry[tile] = cont0 ? value : 0.0;
+            if (cont0) return;
+        }
+        if (row < uint32_t(m)) y[row] = value;
     };
 
     // ---- per-column walk
@@ -560,10 +636,7 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, const int32_t* __restrict__ ro
     for (int j = 0; j < SIGMA; j++) {
         if ((flags >> j) & 1) {
             if (seen) {                                   // a green segment ends
-                uint32_t row = seg_row(seg);
-                if (row < uint32_t(m)) {
-                    if (seg == 0) atomic_add_f64(&y[row], sum); else y[row] = sum;
-                }
+                put(seg, sum);
                 seg++;
             } else {                                      // the red head ends (empty when j == 0)
                 red = sum;
@@ -587,13 +660,53 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, const int32_t* __restrict__ ro
         double dn = __shfl_down(tmp, d, OMEGA);
         if (lane + d <= end) tmp += dn;
     }
-    if (seen) {
-        double total = blue + tmp;
-        uint32_t row = seg_row(seg);
-        bool last_head = (right == 0);                    // the tile's last segment
-        if (row < uint32_t(m)) {
-            if (seg == 0 || last_head) atomic_add_f64(&y[row], total); else y[row] = total;
-        }
+    if (seen) put(seg, blue + tmp);
+}
+
+// ----------------------------------------------------------------------------
+// Second and last launch of an SpMV: adds the carries (the global auxiliary
+// array of Section 4) and writes the zeros of empty rows.
+// One thread per tile, tiles in order across the lanes.  Tiles whose first row
+// is the same row R form a run (a row longer than a tile); a shuffle scan sums
+// the carries of a run and its last lane adds the total to y[R], which already
+// holds the part computed by the tile R starts in.  A run wholly inside one
+// wavefront is a plain read-modify-write (nobody else touches y[R] now); a run
+// cut by a wavefront boundary uses atomic adds, which commute.
+// Rows without nonzeros are stored by no tile; they get their 0 here when the
+// matrix has any (status bit set during conversion).
+// ----------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_spmv_fixup(int m, int ntiles, const int32_t* __restrict__ row_ptr,
+             const uint32_t* __restrict__ tile_ptr, const double* __restrict__ carry,
+             double* __restrict__ y, const uint32_t* __restrict__ status) {
+    const uint32_t st = *status;
+    if (st & BAD_BITS) return;
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = lane_id();
+    if (st & CSR5_STATUS_HAS_EMPTY_ROWS) {
+        const int stride = gridDim.x * blockDim.x;
+        for (int r = gid; r < m; r += stride)
+            if (row_ptr[r] == row_ptr[r + 1]) y[r] = 0.0;
+    }
+    const int t0 = gid - lane;                            // first tile of this wavefront
+    if (t0 >= ntiles) return;
+    const bool live = gid < ntiles;
+    uint32_t R = live ? (tile_ptr[gid] & ROWMASK) : (0xfffffff0u - uint32_t(lane));
+    double cs = live ? carry[gid] : 0.0;
+#pragma unroll
+    for (int d = 1; d < OMEGA; d <<= 1) {
+        double up = __shfl_up(cs, d, OMEGA);
+        uint32_t rup = __shfl_up(R, d, OMEGA);
+        if (lane >= d && rup == R) cs += up;
+    }
+    uint32_t rnext = __shfl_down(R, 1, OMEGA);
+    uint32_t rfirst = __shfl(R, 0, OMEGA);
+    bool run_end = live && ((lane == OMEGA - 1) || (rnext != R));
+    if (run_end && cs != 0.0 && R < uint32_t(m)) {
+        bool ext_left = (rfirst == R) && t0 > 0 && ((tile_ptr[t0 - 1] & ROWMASK) == R);
+        bool ext_right = (lane == OMEGA - 1) && (gid + 1 < ntiles) && ((tile_ptr[gid + 1] & ROWMASK) == R);
+        if (ext_left || ext_right) atomic_add_f64(&y[R], cs);
+        else y[R] += cs;
     }
 }
 
@@ -601,12 +714,14 @@ template <int SIGMA>
 hipError_t launch_spmv(const Geom& g, int m, int nnz, const int32_t* row_ptr, const uint32_t* tile_ptr,
                        const uint32_t* tile_desc, const int32_t* eop, const int32_t* eo,
                        const int32_t* col_idx, const double* val, const double* x, double* y,
-                       const uint32_t* status, hipStream_t s) {
-    uint32_t nb_tiles = uint32_t((g.pc + 3) / 4);
-    uint32_t nb = nb_tiles + ((int64_t(g.pc) * g.T < nnz) ? 1u : 0u);
+                       double* carry, const uint32_t* status, hipStream_t s) {
+    constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
+    uint32_t nb_tiles = uint32_t((g.pc + WAVES - 1) / WAVES);
+    uint32_t has_tail = (int64_t(g.pc) * g.T < nnz) ? 1u : 0u;
+    uint32_t nb = nb_tiles + has_tail;
     if (nb == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_spmv<SIGMA>, dim3(nb), dim3(256), 0, s, m, nnz, g.pc, nb_tiles, row_ptr,
-                       tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, status);
+    hipLaunchKernelGGL(k_spmv<SIGMA>, dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, nb_tiles, has_tail,
+                       row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status);
     return hipGetLastError();
 }
 
@@ -643,6 +758,7 @@ struct csr5_handle_s {
     int32_t* eop;
     int32_t* eo;
     uint32_t* status;
+    double* carry;         // one slot per tile (incomplete one included): cross-tile sums of an SpMV
     void* owned;           // hipMalloc'ed block, or NULL when a workspace was given
     hipStream_t conv_stream;
     bool in_csr5_order;
@@ -651,7 +767,7 @@ struct csr5_handle_s {
 namespace {
 
 struct Layout {
-    size_t off_tile_ptr, off_desc, off_eop, off_eo, off_status, total;
+    size_t off_tile_ptr, off_desc, off_eop, off_eo, off_carry, off_status, total;
     size_t ndesc, eo_cap;
 };
 
@@ -666,6 +782,7 @@ Layout make_layout(int32_t m, const Geom& g) {
     L.off_desc = o;     o += align256(L.ndesc * 4);
     L.off_eop = o;      o += align256((size_t(g.pc) + 1) * 4);
     L.off_eo = o;       o += align256(L.eo_cap * 4);
+    L.off_carry = o;    o += align256((size_t(g.p) + 1) * 8);
     L.off_status = o;   o += 256;
     L.total = o;
     return L;
@@ -751,6 +868,7 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, i
     h->tile_desc = reinterpret_cast<uint32_t*>(basep + L.off_desc);
     h->eop = reinterpret_cast<int32_t*>(basep + L.off_eop);
     h->eo = reinterpret_cast<int32_t*>(basep + L.off_eo);
+    h->carry = reinterpret_cast<double*>(basep + L.off_carry);
     h->status = reinterpret_cast<uint32_t*>(basep + L.off_status);
     h->conv_stream = s;
     h->in_csr5_order = true;
@@ -808,29 +926,78 @@ int csr5_convert(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int3
     return csr5_convert_ex(m, n, nnz, row_ptr, col_idx, val, 0, nullptr, 0, nullptr, CSR5_FLAG_NONE, out);
 }
 
+// One SpMV: the tile kernel, then the carry fix-up.  `ev`, when given, points at
+// three events recorded before, between and after the two launches.
+static int spmv_launch(csr5_handle_t h, const double* x, double* y, hipStream_t s, hipEvent_t* ev) {
+    if (ev && hipEventRecord(ev[0], s) != hipSuccess) return CSR5_EHIP;
+    hipError_t e = hipSuccess;
+    if (h->nnz > 0) {
+        switch (h->g.sigma) {
+#define X(S) case S: e = launch_spmv<S>(h->g, h->m, h->nnz, h->row_ptr, h->tile_ptr, h->tile_desc, h->eop, \
+                                        h->eo, h->col_idx, h->val, x, y, h->carry, h->status, s); break;
+            CSR5_FOR_SIGMA(X)
+#undef X
+            default: e = hipErrorInvalidValue;
+        }
+    }
+    if (e != hipSuccess) return CSR5_EHIP;
+    if (ev && hipEventRecord(ev[1], s) != hipSuccess) return CSR5_EHIP;
+    {
+        // one thread per tile; when the matrix has empty rows the same grid strides over the rows
+        int ntiles = h->g.p;
+        size_t nb = (size_t(ntiles) + 255) / 256;
+        size_t nb_rows = (size_t(h->m) + 255) / 256;
+        if (nb_rows > 512) nb_rows = 512;
+        if (nb < nb_rows) nb = nb_rows;
+        if (nb == 0) nb = 1;
+        hipLaunchKernelGGL(k_spmv_fixup, dim3(uint32_t(nb)), dim3(256), 0, s, h->m, ntiles, h->row_ptr,
+                           h->tile_ptr, h->carry, y, h->status);
+        if (hipGetLastError() != hipSuccess) return CSR5_EHIP;
+    }
+    if (ev && hipEventRecord(ev[2], s) != hipSuccess) return CSR5_EHIP;
+    return CSR5_OK;
+}
+
 int csr5_spmv_ex(csr5_handle_t h, const double* x, double* y, void* hip_stream) {
     if (!h || !h->in_csr5_order) return CSR5_EINVAL;
     if (h->m > 0 && !y) return CSR5_EINVAL;
     if (h->nnz > 0 && !x) return CSR5_EINVAL;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (h->m == 0) return CSR5_OK;
-    {
-        size_t nb = (size_t(h->m) / 2 + 255) / 256;
-        if (nb == 0) nb = 1;
-        if (nb > 4096) nb = 4096;
-        hipLaunchKernelGGL(k_zero_f64, dim3(uint32_t(nb)), dim3(256), 0, s, y, size_t(h->m));
-        if (hipGetLastError() != hipSuccess) return CSR5_EHIP;
+    return spmv_launch(h, x, y, static_cast<hipStream_t>(hip_stream), nullptr);
+}
+
+int csr5_spmv_profile(csr5_handle_t h, const double* x, double* y, void* hip_stream, int reps,
+                      float* ms) {
+    if (!h || !h->in_csr5_order || !ms || reps <= 0 || reps > 100000) return CSR5_EINVAL;
+    if (h->m == 0 || !y || (h->nnz > 0 && !x)) return CSR5_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    size_t nev = size_t(reps) * 3;
+    hipEvent_t* ev = static_cast<hipEvent_t*>(std::calloc(nev, sizeof(hipEvent_t)));
+    if (!ev) return CSR5_ENOMEM;
+    int rc = CSR5_OK;
+    size_t made = 0;
+    for (; made < nev; made++)
+        if (hipEventCreate(&ev[made]) != hipSuccess) { rc = CSR5_EHIP; break; }
+    for (int r = 0; rc == CSR5_OK && r < reps; r++) rc = spmv_launch(h, x, y, s, ev + size_t(r) * 3);
+    if (hipStreamSynchronize(s) != hipSuccess && rc == CSR5_OK) rc = CSR5_EHIP;
+    double acc[2] = {0.0, 0.0};
+    for (int r = 0; rc == CSR5_OK && r < reps; r++) {
+        float a = 0.f, b = 0.f;
+        if (hipEventElapsedTime(&a, ev[size_t(r) * 3], ev[size_t(r) * 3 + 1]) != hipSuccess ||
+            hipEventElapsedTime(&b, ev[size_t(r) * 3 + 1], ev[size_t(r) * 3 + 2]) != hipSuccess) {
+            rc = CSR5_EHIP;
+            break;
+        }
+        acc[0] += a;
+        acc[1] += b;
     }
-    if (h->nnz == 0) return CSR5_OK;
-    hipError_t e;
-    switch (h->g.sigma) {
-#define X(S) case S: e = launch_spmv<S>(h->g, h->m, h->nnz, h->row_ptr, h->tile_ptr, h->tile_desc, h->eop, \
-                                        h->eo, h->col_idx, h->val, x, y, h->status, s); break;
-        CSR5_FOR_SIGMA(X)
-#undef X
-        default: e = hipErrorInvalidValue;
+    for (size_t k = 0; k < made; k++) (void)hipEventDestroy(ev[k]);
+    std::free(ev);
+    if (rc == CSR5_OK) {
+        ms[0] = float(acc[0] / reps);   // tile kernel
+        ms[1] = float(acc[1] / reps);   // carry fix-up
     }
-    return e == hipSuccess ? CSR5_OK : CSR5_EHIP;
+    return rc;
 }
 
 int csr5_spmv(csr5_handle_t h, const double* x, double* y) { return csr5_spmv_ex(h, x, y, nullptr); }
