@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--quick", action="store_true", help="skip the conversion/cold/batch extras")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run plain 256 MiB device copies (a kernel of known traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the method has no multi-GPU part); "
@@ -65,6 +68,14 @@ def main():
         sys.exit(3)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
+
+    if args.copy_probe:
+        src = torch.ones(1 << 25, dtype=torch.float64, device=dev)      # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)                                               # 256 MiB read + 256 MiB written
+        torch.cuda.synchronize()
+        del src, dst
 
     a = wl.config(args.workload)
     st = a.stats()
@@ -244,9 +255,13 @@ def main():
     print(json.dumps(out))
 
 
-# HBM traffic of one tile-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# keyed by (workload, sigma); the profiles/ folder holds the runs these come from.
-MEASURED_TRAFFIC: dict = {}
+# HBM traffic (bytes) of one k_spmv launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# scaled by what the same counters read for a plain copy of known size (2.000 and 1.000),
+# keyed by (workload, sigma).  profiles/k_spmv_hbm_traffic_pmc.md has the runs.
+MEASURED_TRAFFIC: dict = {
+    (2, 16): int((2.000 * 164521.5 + 8014.8) * 1024),     # stencil: 336.9 MB read + 8.2 MB written
+    (3, 6): int((2.000 * 159411.0 + 16100.0) * 1024),     # power-law
+}
 
 
 if __name__ == "__main__":

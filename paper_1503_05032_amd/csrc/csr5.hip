@@ -540,14 +540,23 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     const int tile = int(xcd_remap(blockIdx.x - has_tail, nb_tiles)) * WAVES + wave;
     if (tile >= pc) return;
 
-    // ---- stream the tile: at step j the 64 lanes read 64 consecutive entries
-    const size_t base = size_t(tile) * T + lane;
-    int32_t c[SIGMA];
+    // ---- stream the tile.  val: at step j the 64 lanes read 64 consecutive
+    // doubles, lane i keeping entry (column i, step j).  col_idx is not needed by
+    // its owner lane at all (see the gather below), so it is read with 16-byte
+    // loads in plain memory order: 4 steps of the tile per instruction.
+    const size_t tile_base = size_t(tile) * T;
+    constexpr int NC4 = (SIGMA + 3) / 4;                  // 16-byte col loads per lane
+    typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+    i32x4 c4[NC4];
+    const i32x4* col4 = reinterpret_cast<const i32x4*>(col_idx + tile_base);
+#pragma unroll
+    for (int q = 0; q < NC4; q++) {
+        const int e4 = q * OMEGA + lane;                  // index of the int4 inside the tile
+        c4[q] = (SIGMA % 4 == 0 || e4 < T / 4) ? __builtin_nontemporal_load(&col4[e4]) : i32x4{0, 0, 0, 0};
+    }
     double v[SIGMA];
 #pragma unroll
-    for (int j = 0; j < SIGMA; j++) c[j] = __builtin_nontemporal_load(&col_idx[base + j * OMEGA]);
-#pragma unroll
-    for (int j = 0; j < SIGMA; j++) v[j] = __builtin_nontemporal_load(&val[base + j * OMEGA]);
+    for (int j = 0; j < SIGMA; j++) v[j] = __builtin_nontemporal_load(&val[tile_base + j * OMEGA + lane]);
 
     // ---- descriptor
     const uint32_t tp = tile_ptr[tile];
@@ -578,22 +587,28 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     // ---- gather x.  Lane i owns the CSR entries i*sigma .. i*sigma+sigma-1 of the
     // tile, so at a fixed step the 64 lanes would gather from 64 unrelated
     // places.  Consecutive CSR entries, however, have increasing and often
-    // adjacent columns.  So the column indices take a round trip through LDS:
-    // written by their owners, read back so that lane L holds CSR entries
-    // k*64+L (64 consecutive entries per gather instruction: few distinct cache
-    // lines), x is gathered in that order, and the values return through the
-    // same LDS buffer to the owners.  Rows are padded to an odd pitch.
+    // adjacent columns.  So the column indices are laid out in LDS in CSR order
+    // (entry (i, j) at i*PITCH + j, rows padded to an odd pitch), read back so
+    // that lane L holds CSR entries k*64+L (64 consecutive entries per gather
+    // instruction: few distinct cache lines), x is gathered in that order, and
+    // the values return through the same LDS buffer to the owner lanes.
+    double* const xb = lds[wave];
+    int32_t* const cb = reinterpret_cast<int32_t*>(xb);
     double xv[SIGMA];
-#ifdef CSR5_EXP_DIRECT_GATHER
-#pragma unroll
-    for (int j = 0; j < SIGMA; j++) xv[j] = x[c[j]];
-#else
     {
-        double* xb = lds[wave];
-        int32_t* cb = reinterpret_cast<int32_t*>(xb);
 #pragma unroll
-        for (int j = 0; j < SIGMA; j++) cb[lane * PITCH + j] = c[j];
+        for (int q = 0; q < NC4; q++) {
+            const int m0 = (q * OMEGA + lane) * 4;        // memory offset inside the tile = j*64 + i
+            const int j = m0 / OMEGA, i0 = m0 % OMEGA;
+            if (SIGMA % 4 == 0 || m0 < T) {
+                cb[(i0 + 0) * PITCH + j] = c4[q].x;
+                cb[(i0 + 1) * PITCH + j] = c4[q].y;
+                cb[(i0 + 2) * PITCH + j] = c4[q].z;
+                cb[(i0 + 3) * PITCH + j] = c4[q].w;
+            }
+        }
         wave_sync_lds();
+        int32_t c[SIGMA];
 #pragma unroll
         for (int k = 0; k < SIGMA; k++) {
             const int e = k * OMEGA + lane;
@@ -610,25 +625,13 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
         wave_sync_lds();
 #pragma unroll
         for (int j = 0; j < SIGMA; j++) xv[j] = xb[lane * PITCH + j];
+        wave_sync_lds();
     }
-#endif
 
-    // Store the finished sum of segment number s of this tile.  The bound checks
-    // cannot fail for a consistent descriptor; they keep a corrupted one from
-    // writing outside y.  Only lane 0 ever closes segment 0 (every other column
-    // has the forced first flag before it, so its y_offset is >= 1).
-    auto put = [&](uint32_t s, double value) {
-        uint32_t row;
-        if (!dirty) row = row0 + s;
-        else row = s < nseg_t ? row0 + uint32_t(eo_t[s]) : uint32_t(m);
-        if (s == 0) {
-            carry[tile] = cont0 ? value : 0.0;
-            if (cont0) return;
-        }
-        if (row < uint32_t(m)) y[row] = value;
-    };
-
-    // ---- per-column walk
+    // ---- per-column walk.  Finished segment sums are parked in LDS (the buffer
+    // is free again), slot = segment number inside the tile, and written to y
+    // afterwards, 64 consecutive segments per store instruction.
+    double* const yb = xb;                                // T <= 64*PITCH slots
     double sum = 0.0, red = 0.0;
     bool seen = false;
     uint32_t seg = yo;
@@ -636,7 +639,7 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     for (int j = 0; j < SIGMA; j++) {
         if ((flags >> j) & 1) {
             if (seen) {                                   // a green segment ends
-                put(seg, sum);
+                if (seg < uint32_t(T)) yb[seg] = sum;
                 seg++;
             } else {                                      // the red head ends (empty when j == 0)
                 red = sum;
@@ -660,7 +663,25 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
         double dn = __shfl_down(tmp, d, OMEGA);
         if (lane + d <= end) tmp += dn;
     }
-    if (seen) put(seg, blue + tmp);
+    if (seen && seg < uint32_t(T)) yb[seg] = blue + tmp;
+    // number of segments of the tile = flags before the last column + its own
+    uint32_t nseg = __shfl(seen ? seg + 1 : seg, OMEGA - 1, OMEGA);
+    if (nseg > uint32_t(T)) nseg = T;
+    if (dirty && nseg > nseg_t) nseg = nseg_t;            // cannot happen for a consistent format
+    wave_sync_lds();
+
+    // ---- write the tile's rows.  Segment s is row tile_ptr + s, or
+    // tile_ptr + empty_offset[s] when the tile holds empty rows.  Segment 0 goes
+    // to the carry array when it continues an earlier tile's row.
+    for (uint32_t s0 = 0; s0 < nseg; s0 += OMEGA) {
+        const uint32_t sg = s0 + lane;
+        if (sg < nseg) {
+            const double value = yb[sg];
+            const uint32_t row = row0 + (dirty ? uint32_t(eo_t[sg]) : sg);
+            if (sg == 0) carry[tile] = cont0 ? value : 0.0;
+            if ((sg != 0 || !cont0) && row < uint32_t(m)) y[row] = value;
+        }
+    }
 }
 
 // ----------------------------------------------------------------------------
@@ -828,6 +849,9 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, i
     if (m < 0 || n < 0 || nnz < 0) return CSR5_EINVAL;
     if (!row_ptr) return CSR5_EINVAL;                      // row_ptr has m+1 >= 1 entries
     if (nnz > 0 && (!col_idx || !val || m == 0 || n == 0)) return CSR5_EINVAL;
+    // the kernels read col_idx with 16-byte and val with 8-byte accesses
+    if ((reinterpret_cast<uintptr_t>(col_idx) & 15) || (reinterpret_cast<uintptr_t>(val) & 7) ||
+        (reinterpret_cast<uintptr_t>(row_ptr) & 3)) return CSR5_EINVAL;
     if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
     if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX) return CSR5_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);

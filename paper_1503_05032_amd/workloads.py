@@ -133,40 +133,77 @@ def stencil27(g=100, seed=1) -> Csr:
 # --------------------------------------------------------------------------
 # config 3: power-law
 # --------------------------------------------------------------------------
-def powerlaw(m=2_000_000, a_len=2.0, a_col=1.5, max_len=200_000, topup_above=1000, seed=2) -> Csr:
-    """Square power-law matrix.  Row length = clip(Zipf(a_len), 1, max_len).
-    Columns = (Zipf(a_col) - 1) mod n, i.e. strongly preferential toward low ids;
-    duplicates inside a row are dropped.  Dropping shrinks the very long rows a
-    lot (few distinct values under Zipf), so rows whose target length exceeds
-    `topup_above` are topped up with uniform columns until they reach the target.
-    Values and x ~ U[0, 1]."""
+def _zipf_distinct_row(rng, target, n, a_col):
+    """Distinct columns of one long power-law row, drawn in the "many draws" limit.
+
+    Drawing N times from Zipf(a) over {1..n} and dropping duplicates keeps
+    column k with probability 1 - exp(-tau * k^-a) (tau = N / zeta-normaliser),
+    independently of the other columns to a very good approximation.  tau is
+    chosen so that the expected number of distinct columns equals `target`
+    (closed form of the sum for n -> infinity, minus the part beyond n).  The
+    head (where the probability is not small) is drawn column by column; the
+    far tail, where the probability is ~ tau * k^-a, as a Poisson process.
+    Returns sorted distinct 0-based columns."""
+    from math import gamma
+    g = gamma(1.0 - 1.0 / a_col)                    # a=1.5: Gamma(1/3)
+    pw = 1.0 / a_col                                # distinct(tau) ~ g * tau^(1/a)
+    tail_c = 1.0 / (a_col - 1.0)                    # integral_n^inf k^-a dk = tail_c * n^(1-a)
+
+    def expected(tau):
+        return g * tau ** pw - tau * tail_c * n ** (1.0 - a_col)
+    lo, hi = 1.0, 1.0
+    while expected(hi) < target and hi < 1e18:
+        hi *= 2.0
+    for _ in range(80):
+        mid = 0.5 * (lo + hi)
+        if expected(mid) < target:
+            lo = mid
+        else:
+            hi = mid
+    tau = 0.5 * (lo + hi)
+    K = int(min(n, max(64, 8.0 * tau ** pw)))       # beyond K the keep-probability is < 8^-a
+    k = np.arange(1, K + 1, dtype=np.float64)
+    keep = rng.random(K) < -np.expm1(-tau * k ** (-a_col))
+    head = np.nonzero(keep)[0]                      # 0-based columns
+    if K < n:
+        e = 1.0 - a_col                             # cumulative intensity tau*tail_c*(K^e - k^e)
+        lam_max = tau * tail_c * (K ** e - float(n) ** e)
+        cnt = rng.poisson(lam_max)
+        s = np.sort(rng.random(cnt)) * lam_max
+        kk = (K ** e - s / (tau * tail_c)) ** (1.0 / e)
+        tail = np.unique(np.clip(np.ceil(kk).astype(np.int64), K + 1, n)) - 1
+        return np.concatenate([head, tail]).astype(np.int32)
+    return head.astype(np.int32)
+
+
+def powerlaw(m=2_000_000, a_len=2.0, a_col=1.5, max_len=200_000, long_above=1000, seed=2) -> Csr:
+    """Square power-law matrix.  Row length target = clip(Zipf(a_len), 1, max_len).
+    Columns are preferential toward low ids: (Zipf(a_col) - 1) mod n, duplicates
+    inside a row dropped (so short rows end up a little shorter than their
+    target).  A row whose target exceeds `long_above` would need an astronomical
+    number of draws to collect that many distinct Zipf values, so it is drawn
+    directly as the distinct set such draws produce (_zipf_distinct_row), with
+    the expected length equal to the target.  Values and x ~ U[0, 1]."""
     rng = np.random.default_rng(seed)
     n = m
     max_len = min(max_len, n)
     target = np.clip(rng.zipf(a_len, size=m), 1, max_len).astype(np.int64)
-    rows = np.repeat(np.arange(m, dtype=np.int64), target)
+    long_rows = np.nonzero(target > long_above)[0]
+    short_t = target.copy()
+    short_t[long_rows] = 0
+    rows = np.repeat(np.arange(m, dtype=np.int64), short_t)
     cols = (rng.zipf(a_col, size=rows.shape[0]) - 1) % n
     lens, c = _dedupe_sorted(rows, cols, m, n)
     del rows, cols
-    long_rows = np.nonzero(target > topup_above)[0]
     if long_rows.size:
         start = np.zeros(m + 1, dtype=np.int64)
         np.cumsum(lens, out=start[1:])
         pieces = []
         prev = 0
         for r in long_rows:
-            have = c[start[r]:start[r + 1]]
-            need = int(target[r])
-            got = np.unique(have)
-            while got.size < need:
-                extra = rng.integers(0, n, size=2 * (need - got.size) + 16)
-                got = np.unique(np.concatenate([got, extra]))
-                if got.size > need:
-                    # drop surplus from the uniform extras only (keep it simple: random subset)
-                    drop = rng.choice(got.size, size=got.size - need, replace=False)
-                    got = np.delete(got, drop)
+            got = _zipf_distinct_row(rng, int(target[r]), n, a_col)
             pieces.append(c[start[prev]:start[r]])
-            pieces.append(got.astype(np.int32))
+            pieces.append(got)
             lens[r] = got.size
             prev = r + 1
         pieces.append(c[start[prev]:])
