@@ -54,8 +54,10 @@ enum {
 
 /*
  * sigma from nnz/row (Section 3.2): the paper's four-way rule with bounds
- * <r, s, t, u> chosen for MI355X; nnz/row is the integer quotient nnz/m.
- * Pure host arithmetic.
+ * <r, s, t, u> = <8, 16, 256, 16> measured on MI355X; nnz/row is the integer
+ * quotient nnz/m.  One addition: when nnz/row <= t and the matrix would have
+ * fewer than 16384 tiles at the sigma the rule gives, sigma = r (small matrices
+ * need the parallelism more than the amortisation).  Pure host arithmetic.
  */
 int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
 
@@ -164,6 +166,20 @@ int csr5_get_info(csr5_handle_t h, int32_t *omega, int32_t *sigma, int32_t *p, i
  */
 int csr5_get_arrays(csr5_handle_t h, const uint32_t **tile_ptr, const uint32_t **tile_desc,
                     const int32_t **empty_offset_ptr, const int32_t **empty_offset);
+
+/*
+ * CSR row-block baselines on the plain CSR arrays (Section 2.2.1): CSR-scalar is
+ * Algorithm 1 with one thread per row; CSR-vector reduces each row with
+ * lanes_per_row lanes (2, 4, ..., 64; 0 = smallest power of two >= nnz/m).
+ * They exist for the iteration-scenario comparison of Section 5.5 (cost of
+ * staying in CSR against converting to CSR5) and do not touch any handle.
+ * y double[m] is overwritten.  Asynchronous on the stream.
+ */
+int csr5_baseline_csr_scalar(int32_t m, const int32_t *row_ptr, const int32_t *col_idx, const double *val,
+                             const double *x, double *y, void *hip_stream);
+int csr5_baseline_csr_vector(int32_t m, int32_t nnz, const int32_t *row_ptr, const int32_t *col_idx,
+                             const double *val, const double *x, double *y, int32_t lanes_per_row,
+                             void *hip_stream);
 
 /*
  * Copies one of the handle's arrays to HOST memory (blocking; waits for the

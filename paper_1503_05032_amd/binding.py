@@ -29,7 +29,7 @@ CSR5_ARRAY_TILE_PTR, CSR5_ARRAY_TILE_DESC, CSR5_ARRAY_EMPTY_OFFSET_PTR, CSR5_ARR
 SYMBOLS = [
     "csr5_sigma_auto", "csr5_workspace_bytes", "csr5_convert", "csr5_convert_ex", "csr5_spmv",
     "csr5_spmv_ex", "csr5_spmv_profile", "csr5_to_csr", "csr5_free", "csr5_status", "csr5_get_info", "csr5_get_arrays",
-    "csr5_read_array", "csr5_strerror",
+    "csr5_read_array", "csr5_strerror", "csr5_baseline_csr_scalar", "csr5_baseline_csr_vector",
 ]
 
 
@@ -80,6 +80,10 @@ def load():
     lib.csr5_get_arrays.argtypes = [vp] + [C.POINTER(vp)] * 4
     lib.csr5_read_array.restype = C.c_int
     lib.csr5_read_array.argtypes = [vp, C.c_int, vp, sz]
+    lib.csr5_baseline_csr_scalar.restype = C.c_int
+    lib.csr5_baseline_csr_scalar.argtypes = [i32, vp, vp, vp, vp, vp, vp]
+    lib.csr5_baseline_csr_vector.restype = C.c_int
+    lib.csr5_baseline_csr_vector.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, vp]
     lib.csr5_strerror.restype = C.c_char_p
     lib.csr5_strerror.argtypes = [C.c_int]
     _lib = lib
@@ -186,6 +190,17 @@ def csr5_get_arrays(h):
     v = [C.c_void_p() for _ in range(4)]
     _chk(load().csr5_get_arrays(h, *[C.byref(a) for a in v]), "csr5_get_arrays", True)
     return dict(zip(["tile_ptr", "tile_desc", "empty_offset_ptr", "empty_offset"], [a.value for a in v]))
+
+
+def csr5_baseline_csr_scalar(m, row_ptr, col_idx, val, x, y, stream=None, check=True):
+    return _chk(load().csr5_baseline_csr_scalar(m, _ptr(row_ptr), _ptr(col_idx), _ptr(val), _ptr(x), _ptr(y),
+                                                _stream(stream)), "csr5_baseline_csr_scalar", check)
+
+
+def csr5_baseline_csr_vector(m, nnz, row_ptr, col_idx, val, x, y, lanes_per_row=0, stream=None, check=True):
+    return _chk(load().csr5_baseline_csr_vector(m, nnz, _ptr(row_ptr), _ptr(col_idx), _ptr(val), _ptr(x),
+                                                _ptr(y), int(lanes_per_row), _stream(stream)),
+                "csr5_baseline_csr_vector", check)
 
 
 def csr5_read_array(h, which):

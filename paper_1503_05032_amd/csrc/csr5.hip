@@ -25,8 +25,12 @@ constexpr uint32_t BAD_BITS = CSR5_STATUS_BAD_ROW_PTR | CSR5_STATUS_BAD_COL_IDX;
 constexpr int NUM_XCD = 8;  // MI355X: 8 accelerator dies, each with its own L2
 
 // sigma rule constants <r, s, t, u> for MI355X (Section 3.2 leaves them to the
-// hardware; see csr5_sigma_auto).
-constexpr int RULE_R = 4, RULE_S = 16, RULE_T = 256, RULE_U = 16;
+// hardware; measured with calibrate.py, see csr5_sigma_auto).
+constexpr int RULE_R = 8, RULE_S = 16, RULE_T = 256, RULE_U = 16;
+// A matrix with fewer tiles than this at sigma > r gets sigma = r: the chip holds
+// 256 CUs x 16 wavefronts of this kernel, and below about four rounds of them the
+// ramp-up and the last partial round dominate.
+constexpr int64_t RULE_MIN_TILES = 4 * 256 * 16;
 
 inline int ceil_log2_host(int64_t v) {
     int b = 0;
@@ -758,6 +762,39 @@ hipError_t launch_transpose(const Geom& g, int n, int nnz, int32_t* col_idx, dou
     return hipGetLastError();
 }
 
+// ----------------------------------------------------------------------------
+// CSR row-block baselines (Section 2.2.1), for the iteration-scenario comparison
+// of Section 5.5: the cost of staying in CSR.  They read the untouched CSR
+// arrays and have nothing to do with the CSR5 path.
+//  * CSR-scalar (Algorithm 1): one thread per row.
+//  * CSR-vector: LANES lanes per row (a power of two up to the wavefront),
+//    lane-strided loads, shuffle reduction.
+// ----------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_csr_scalar(int m, const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+             const double* __restrict__ val, const double* __restrict__ x, double* __restrict__ y) {
+    int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= m) return;
+    double acc = 0.0;
+    for (int k = row_ptr[r], e = row_ptr[r + 1]; k < e; k++) acc = fma(val[k], x[col_idx[k]], acc);
+    y[r] = acc;
+}
+
+template <int LANES>
+__global__ void __launch_bounds__(256)
+k_csr_vector(int m, const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+             const double* __restrict__ val, const double* __restrict__ x, double* __restrict__ y) {
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int r = gid / LANES, sub = gid % LANES;
+    double acc = 0.0;
+    if (r < m)
+        for (int k = row_ptr[r] + sub, e = row_ptr[r + 1]; k < e; k += LANES)
+            acc = fma(val[k], x[col_idx[k]], acc);
+#pragma unroll
+    for (int d = LANES / 2; d >= 1; d >>= 1) acc += __shfl_down(acc, d, LANES);
+    if (r < m && sub == 0) y[r] = acc;
+}
+
 #define CSR5_FOR_SIGMA(X)                                                                          \
     X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17)   \
     X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25) X(26) X(27) X(28) X(29) X(30) X(31) X(32)      \
@@ -827,10 +864,10 @@ const char* csr5_strerror(int code) {
 int32_t csr5_sigma_auto(int64_t nnz, int64_t m) {
     if (m <= 0 || nnz <= 0) return RULE_R;
     int64_t q = nnz / m;
-    if (q <= RULE_R) return RULE_R;
-    if (q <= RULE_S) return int32_t(q);
-    if (q <= RULE_T) return RULE_S;
-    return RULE_U;
+    if (q > RULE_T) return RULE_U;
+    int32_t sigma = q <= RULE_R ? RULE_R : (q <= RULE_S ? int32_t(q) : RULE_S);
+    if (sigma > RULE_R && nnz < RULE_MIN_TILES * OMEGA * sigma) sigma = RULE_R;
+    return sigma;
 }
 
 size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma) {
@@ -1084,6 +1121,39 @@ int csr5_get_arrays(csr5_handle_t h, const uint32_t** tile_ptr, const uint32_t**
     if (empty_offset_ptr) *empty_offset_ptr = h->eop;
     if (empty_offset) *empty_offset = h->eo;
     return CSR5_OK;
+}
+
+int csr5_baseline_csr_scalar(int32_t m, const int32_t* row_ptr, const int32_t* col_idx, const double* val,
+                             const double* x, double* y, void* hip_stream) {
+    if (m < 0 || !row_ptr || (m > 0 && !y)) return CSR5_EINVAL;
+    if (m == 0) return CSR5_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(k_csr_scalar, dim3(uint32_t((size_t(m) + 255) / 256)), dim3(256), 0, s, m, row_ptr,
+                       col_idx, val, x, y);
+    return hipGetLastError() == hipSuccess ? CSR5_OK : CSR5_EHIP;
+}
+
+int csr5_baseline_csr_vector(int32_t m, int32_t nnz, const int32_t* row_ptr, const int32_t* col_idx,
+                             const double* val, const double* x, double* y, int32_t lanes_per_row,
+                             void* hip_stream) {
+    if (m < 0 || nnz < 0 || !row_ptr || (m > 0 && !y)) return CSR5_EINVAL;
+    if (m == 0) return CSR5_OK;
+    if (lanes_per_row == 0) {   // smallest power of two >= nnz/row, between 2 and 64
+        int64_t q = nnz / m;
+        lanes_per_row = 2;
+        while (lanes_per_row < 64 && lanes_per_row < q) lanes_per_row *= 2;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    size_t threads = size_t(m) * size_t(lanes_per_row);
+    dim3 grid(uint32_t((threads + 255) / 256)), block(256);
+    if (threads / 256 >= 0x7fffffffull) return CSR5_EINVAL;
+    switch (lanes_per_row) {
+#define X(L) case L: hipLaunchKernelGGL(k_csr_vector<L>, grid, block, 0, s, m, row_ptr, col_idx, val, x, y); break;
+        X(2) X(4) X(8) X(16) X(32) X(64)
+#undef X
+        default: return CSR5_EINVAL;
+    }
+    return hipGetLastError() == hipSuccess ? CSR5_OK : CSR5_EHIP;
 }
 
 int csr5_read_array(csr5_handle_t h, int which, void* dst_host, size_t bytes) {

@@ -31,18 +31,24 @@ def test_header_symbols_exported(lib):
 
 
 def test_sigma_rule_matches_paper_shape(lib):
-    # the library's rule is the four-way map of Section 3.2; its constants are the
-    # library's own.  Recover them from its behaviour and compare with the oracle's rule.
-    m = 1000
+    # The library's rule is the four-way map of Section 3.2 with its own constants.
+    # Recover them from its behaviour on a matrix large enough that the
+    # small-matrix clamp is inactive, and compare with the oracle's rule.
+    m = 4_000_000
     vals = [B.csr5_sigma_auto(q * m, m) for q in range(0, 400)]
     r = vals[0]
     s = max(vals)
-    t = max(q for q in range(400) if vals[q] == s)
+    t = max(q for q in range(400) if vals[q] == s and all(v == s for v in vals[s:q + 1]))
     u = vals[399]
     for q in range(0, 400):
         assert vals[q] == oracle.sigma_rule(q * m, m, r, s, t, u), q
     assert B.csr5_sigma_auto(0, 0) == r
     assert all(B.CSR5_SIGMA_MIN <= v <= B.CSR5_SIGMA_MAX for v in vals)
+    # small-matrix clamp: fewer than 16384 tiles at sigma > r  ->  r  (only below t)
+    assert B.csr5_sigma_auto(12 * 1000, 1000) == r
+    assert B.csr5_sigma_auto(16384 * 64 * 12, 16384 * 64) == 12
+    assert B.csr5_sigma_auto(16384 * 64 * 12 - 12, 16384 * 64 - 1) == r
+    assert B.csr5_sigma_auto(1000 * 1000, 1000) == u
 
 
 def test_workspace_bytes(lib):

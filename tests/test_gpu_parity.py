@@ -154,3 +154,31 @@ def test_repeatability_within_tolerance():
     assert np.all(np.abs(ys[0] - ys[1]) <= 2e-12 * s + 1e-300)
     assert np.all(np.abs(ys[0] - ys[2]) <= 2e-12 * s + 1e-300)
     B.csr5_free(h)
+
+
+def _check_y(y, a, label):
+    y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
+    err = np.abs(y - y_ref)
+    bad = np.nonzero(~(err <= 1e-12 * s + 1e-300))[0]
+    assert bad.size == 0, (label, int(bad.size), int(bad[0]))
+
+
+def test_csr_baselines_match_oracle():
+    """CSR-scalar and CSR-vector (Section 2.2.1) on the untouched CSR arrays."""
+    mats = wl.edge_cases(64 * 4) + [wl.config(1), wl.config(3, scale=0.01), wl.config(4, scale=0.01)]
+    for a in mats:
+        if a.m == 0:
+            continue
+        say("baseline", a.name, a.m, a.nnz)
+        d = DeviceCsr(a)
+        d.y.fill_(float("nan"))
+        B.csr5_baseline_csr_scalar(a.m, d.row_ptr, d.col_idx, d.val, d.x, d.y)
+        torch.cuda.synchronize()
+        _check_y(d.y.cpu().numpy()[:a.m], a, (a.name, "scalar"))
+        for lanes in (0, 2, 4, 8, 16, 32, 64):
+            d.y.fill_(float("nan"))
+            B.csr5_baseline_csr_vector(a.m, a.nnz, d.row_ptr, d.col_idx, d.val, d.x, d.y, lanes_per_row=lanes)
+            torch.cuda.synchronize()
+            _check_y(d.y.cpu().numpy()[:a.m], a, (a.name, "vector", lanes))
+    assert B.csr5_baseline_csr_vector(5, 5, d.row_ptr, d.col_idx, d.val, d.x, d.y, lanes_per_row=3,
+                                      check=False) == B.CSR5_EINVAL
