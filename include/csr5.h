@@ -89,15 +89,18 @@ size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma);
  *               empty_offset with its per-tile start array.
  *
  * csr5_convert picks sigma itself, allocates with hipMalloc, runs on the default
- * stream and checks row_ptr[0] and row_ptr[m] on the host (one blocking copy).
+ * stream, checks row_ptr[0] and row_ptr[m] on the host before it starts and
+ * waits for the conversion's device-side checks at the end: it BLOCKS, and
+ * returns CSR5_EINVAL (col_idx and val restored to CSR order) when row_ptr is
+ * inconsistent or a column index is out of range.
  *
  * csr5_convert_ex: sigma = 0 means automatic.  If workspace != NULL the
  * handle's arrays are carved from it (workspace_bytes must be at least
  * csr5_workspace_bytes(m, nnz, sigma); the memory stays the caller's and must
- * outlive the handle), and no allocation happens on the device.  With
- * CSR5_FLAG_NO_HOST_CHECK the call does not synchronise.  Consistency of the
- * whole row_ptr and the range of col_idx are checked on the device during
- * conversion; read the verdict with csr5_status.
+ * outlive the handle), and no allocation happens on the device.  Without
+ * CSR5_FLAG_NO_HOST_CHECK it blocks and validates like csr5_convert.  With the
+ * flag it only enqueues work: consistency of row_ptr and the range of col_idx
+ * are still checked on the device; read the verdict with csr5_status.
  */
 int csr5_convert(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, int32_t *col_idx,
                  double *val, csr5_handle_t *out);

@@ -978,6 +978,22 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, i
         delete h;
         return CSR5_EHIP;
     }
+    if (!(flags & CSR5_FLAG_NO_HOST_CHECK)) {
+        // blocking variant: wait for the device-side verdict; on bad input undo the
+        // transposition and refuse
+        uint32_t st = 0;
+        int rc = csr5_status(h, &st);
+        if (rc == CSR5_OK && (st & BAD_BITS)) {
+            (void)csr5_to_csr(h, hip_stream);
+            (void)hipStreamSynchronize(s);
+            rc = CSR5_EINVAL;
+        }
+        if (rc != CSR5_OK) {
+            if (h->owned) (void)hipFree(h->owned);
+            delete h;
+            return rc;
+        }
+    }
     *out = h;
     return CSR5_OK;
 }

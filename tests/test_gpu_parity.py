@@ -119,12 +119,23 @@ def test_error_paths():
     assert rc == B.CSR5_ENOMEM and not h
     assert B.csr5_spmv(None, d.x, d.y, check=False) == B.CSR5_EINVAL
     assert B.csr5_free(None) == B.CSR5_OK
-    # decreasing row_ptr in the middle: device-side validation reports it, spmv leaves y alone
+    # decreasing row_ptr in the middle
     rp = a.row_ptr.copy()
     rp[100], rp[101] = rp[101] + 3, rp[100]
     d2 = DeviceCsr(a)
     d2.row_ptr = torch.from_numpy(rp).to("cuda:0")
-    h = B.csr5_convert_ex(a.m, a.n, a.nnz, d2.row_ptr, d2.col_idx, d2.val, sigma=4)
+    # (a) blocking variant: refused, col_idx / val back in CSR order
+    rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz, d2.row_ptr, d2.col_idx, d2.val, sigma=4, check=False)
+    assert rc == B.CSR5_EINVAL and not h
+    assert np.array_equal(d2.col_idx.cpu().numpy(), a.col_idx)
+    assert np.array_equal(d2.val.cpu().numpy(), a.val)
+    # (b) asynchronous variant: a handle, the verdict in the status word, SpMV touches nothing
+    h = B.csr5_convert_ex(a.m, a.n, a.nnz, d2.row_ptr, d2.col_idx, d2.val, sigma=4,
+                          flags=B.CSR5_FLAG_NO_HOST_CHECK)
+    d2.y.fill_(123.0)
+    B.csr5_spmv(h, d2.x, d2.y)
+    torch.cuda.synchronize()
+    assert np.all(d2.y.cpu().numpy() == 123.0)
     assert B.csr5_status(h) & B.CSR5_STATUS_BAD_ROW_PTR
     B.csr5_free(h)
     # a column index out of range
@@ -132,13 +143,16 @@ def test_error_paths():
     ci[77] = a.n + 5
     d3 = DeviceCsr(a)
     d3.col_idx = torch.from_numpy(ci).to("cuda:0")
-    h = B.csr5_convert_ex(a.m, a.n, a.nnz, d3.row_ptr, d3.col_idx, d3.val, sigma=4)
+    rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz, d3.row_ptr, d3.col_idx, d3.val, sigma=4, check=False)
+    assert rc == B.CSR5_EINVAL and not h
+    assert np.array_equal(d3.col_idx.cpu().numpy(), ci)
+    h = B.csr5_convert_ex(a.m, a.n, a.nnz, d3.row_ptr, d3.col_idx, d3.val, sigma=4,
+                          flags=B.CSR5_FLAG_NO_HOST_CHECK)
     assert B.csr5_status(h) & B.CSR5_STATUS_BAD_COL_IDX
     d3.y.fill_(123.0)
     B.csr5_spmv(h, d3.x, d3.y)
     torch.cuda.synchronize()
-    yy = d3.y.cpu().numpy()
-    assert np.all((yy == 0.0) | (yy == 123.0))      # zero-filled at most; nothing gathered
+    assert np.all(d3.y.cpu().numpy() == 123.0)      # nothing gathered, nothing stored
     B.csr5_free(h)
 
 
