@@ -131,8 +131,9 @@ k_tile_ptr(int m, const int32_t* __restrict__ row_ptr, int T, int p, uint32_t* _
 __global__ void __launch_bounds__(256)
 k_rows(int m, int nnz, const int32_t* __restrict__ row_ptr, int sigma, int T, int W, int p, int pc,
        uint32_t* tile_ptr, uint32_t* desc, uint32_t* status) {
-    int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= m) return;
+    const int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (g >= int64_t(m)) return;
+    const int r = int(g);
     int a = row_ptr[r], b = row_ptr[r + 1];
     bool bad = (a < 0) || (b < a) || (b > nnz) || (r == 0 && a != 0) || (r == m - 1 && b != nnz);
     if (bad) {
@@ -709,8 +710,8 @@ k_spmv_fixup(int m, int ntiles, const int32_t* __restrict__ row_ptr,
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = lane_id();
     if (st & CSR5_STATUS_HAS_EMPTY_ROWS) {
-        const int stride = gridDim.x * blockDim.x;
-        for (int r = gid; r < m; r += stride)
+        const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+        for (int64_t r = gid; r < int64_t(m); r += stride)
             if (row_ptr[r] == row_ptr[r + 1]) y[r] = 0.0;
     }
     const int t0 = gid - lane;                            // first tile of this wavefront
@@ -773,8 +774,9 @@ hipError_t launch_transpose(const Geom& g, int n, int nnz, int32_t* col_idx, dou
 __global__ void __launch_bounds__(256)
 k_csr_scalar(int m, const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
              const double* __restrict__ val, const double* __restrict__ x, double* __restrict__ y) {
-    int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= m) return;
+    const int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (g >= int64_t(m)) return;
+    const int r = int(g);
     double acc = 0.0;
     for (int k = row_ptr[r], e = row_ptr[r + 1]; k < e; k++) acc = fma(val[k], x[col_idx[k]], acc);
     y[r] = acc;
@@ -784,15 +786,16 @@ template <int LANES>
 __global__ void __launch_bounds__(256)
 k_csr_vector(int m, const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
              const double* __restrict__ val, const double* __restrict__ x, double* __restrict__ y) {
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-    const int r = gid / LANES, sub = gid % LANES;
+    const int64_t gid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t r = gid / LANES;
+    const int sub = int(gid % LANES);
     double acc = 0.0;
-    if (r < m)
+    if (r < int64_t(m))
         for (int k = row_ptr[r] + sub, e = row_ptr[r + 1]; k < e; k += LANES)
             acc = fma(val[k], x[col_idx[k]], acc);
 #pragma unroll
     for (int d = LANES / 2; d >= 1; d >>= 1) acc += __shfl_down(acc, d, LANES);
-    if (r < m && sub == 0) y[r] = acc;
+    if (r < int64_t(m) && sub == 0) y[r] = acc;
 }
 
 #define CSR5_FOR_SIGMA(X)                                                                          \

@@ -196,3 +196,37 @@ def test_csr_baselines_match_oracle():
             _check_y(d.y.cpu().numpy()[:a.m], a, (a.name, "vector", lanes))
     assert B.csr5_baseline_csr_vector(5, 5, d.row_ptr, d.col_idx, d.val, d.x, d.y, lanes_per_row=3,
                                       check=False) == B.CSR5_EINVAL
+
+
+def test_side_stream_and_graph_replay():
+    """csr5_spmv_ex only enqueues kernels: it runs on any stream and can be
+    captured into a HIP graph; every replay must equal the eager result."""
+    a = wl.config(4, scale=0.02)           # has empty rows, long rows and an incomplete tile
+    d = DeviceCsr(a)
+    h = convert(d, sigma=0)
+    y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        d.y.fill_(float("nan"))
+        B.csr5_spmv_ex(h, d.x, d.y)          # binding passes the current (= side) stream
+    side.synchronize()
+    assert np.all(np.abs(d.y.cpu().numpy()[:a.m] - y_ref) <= 1e-12 * s + 1e-300)
+    # graph capture + replays with the eager path in between
+    xs = [np.random.default_rng(k).standard_normal(a.n) for k in range(3)]
+    xg = d.x.clone()
+    yg = torch.empty_like(d.y)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        B.csr5_spmv_ex(h, xg, yg)
+    for k, xk in enumerate(xs):
+        xg.copy_(torch.from_numpy(xk))
+        yg.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        got = yg.cpu().numpy()[:a.m].copy()
+        check_spmv(d, h, ("eager", k), x=xk)                 # eager work between replays
+        yk, sk = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, xk)
+        assert np.all(np.abs(got - yk) <= 1e-12 * sk + 1e-300), ("replay", k)
+    B.csr5_free(h)
