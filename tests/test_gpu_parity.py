@@ -230,3 +230,33 @@ def test_side_stream_and_graph_replay():
         yk, sk = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, xk)
         assert np.all(np.abs(got - yk) <= 1e-12 * sk + 1e-300), ("replay", k)
     B.csr5_free(h)
+
+
+def test_random_matrices():
+    """Randomised parity: mixed row-length distributions (empty runs, short rows,
+    a few rows longer than a tile), random shapes and sigma."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        sigma = int(rng.integers(1, 49))
+        T = 64 * sigma
+        m = int(rng.integers(1, 3000))
+        n = int(rng.integers(1, 5000))
+        kind = case % 4
+        if kind == 0:
+            lens = rng.geometric(0.2, size=m) - 1
+        elif kind == 1:
+            lens = rng.integers(0, 4, size=m) * (rng.random(m) < 0.5)
+        elif kind == 2:
+            lens = rng.integers(0, 30, size=m)
+            lens[rng.integers(0, m, size=3)] = rng.integers(T, 3 * T + 2, size=3)
+        else:
+            lens = np.zeros(m, dtype=np.int64)
+            idx = rng.integers(0, m, size=max(1, m // 50))
+            lens[idx] = rng.integers(1, 2 * T, size=idx.size)
+        a = wl.from_row_lengths(lens, n, seed=case, name=f"random{case}")
+        say("random", case, "sigma", sigma, a.m, a.n, a.nnz)
+        d = DeviceCsr(a)
+        h = convert(d, sigma=sigma, use_workspace=bool(case % 2))
+        check_format(d, h, (a.name, sigma))
+        check_spmv(d, h, (a.name, sigma))
+        B.csr5_free(h)
