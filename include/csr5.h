@@ -54,10 +54,11 @@ enum {
 
 /*
  * sigma from nnz/row (Section 3.2): the paper's four-way rule with bounds
- * <r, s, t, u> = <8, 16, 256, 16> measured on MI355X; nnz/row is the integer
- * quotient nnz/m.  One addition: when nnz/row <= t and the matrix would have
- * fewer than 16384 tiles at the sigma the rule gives, sigma = r (small matrices
- * need the parallelism more than the amortisation).  Pure host arithmetic.
+ * <r, s, t, u> = <16, 16, 256, 16> measured on MI355X (nnz/row is the integer
+ * quotient nnz/m; on this GPU the best sigma turned out not to depend on it).
+ * One addition: when nnz/row <= t and the matrix would have fewer than 16384
+ * tiles at that sigma, sigma = 8 (a small matrix needs the parallelism more than
+ * the amortisation).  Pure host arithmetic.
  */
 int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
 

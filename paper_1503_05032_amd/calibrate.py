@@ -2,13 +2,15 @@
 nnz/row -> sigma rule are hardware constants "obtained through some simple
 benchmarks"; Section 5.4 / Figure 9: auto-tuned sigma against the best sigma).
 
-    python -m paper_1503_05032_amd.calibrate [--sigmas 4..48] [--workloads 1,2,3,4,5,probes]
+    python -m paper_1503_05032_amd.calibrate [--sigmas 4..48] [--workloads 1,2,3,4,5,probes,bigprobes]
 
 For every matrix it converts at each sigma, times csr5_spmv (HIP events around
 back-to-back calls) and prints one table row per matrix: nnz/row, the best
 sigma, the time at the library's automatic sigma and the loss against the best.
 The probe matrices have fixed row lengths 1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 64,
-128, 256, 512, 2048 (uniform columns), which is what the rule is a function of.
+128, 256, 512, 2048 (banded random columns), which is what the rule is a function
+of, at about 8 M nonzeros ("probes": fewer tiles than the chip holds wavefronts
+for) and, for a few lengths, at about 60 M ("bigprobes").
 Needs a GPU.  Results are facts about the machine, not parity items.
 """
 from __future__ import annotations
@@ -93,6 +95,11 @@ def main():
     for tok in args.workloads.split(","):
         if tok == "probes":
             mats += [probe_matrix(L) for L in (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 64, 128, 256, 512, 2048)]
+        elif tok == "bigprobes":
+            for L in (1, 2, 4, 8, 12, 32, 128):
+                a = probe_matrix(L, nnz_target=60_000_000)
+                a.name = "big_" + a.name
+                mats.append(a)
         else:
             mats.append(wl.config(int(tok)))
     raw = {}

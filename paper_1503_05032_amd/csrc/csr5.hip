@@ -25,12 +25,15 @@ constexpr uint32_t BAD_BITS = CSR5_STATUS_BAD_ROW_PTR | CSR5_STATUS_BAD_COL_IDX;
 constexpr int NUM_XCD = 8;  // MI355X: 8 accelerator dies, each with its own L2
 
 // sigma rule constants <r, s, t, u> for MI355X (Section 3.2 leaves them to the
-// hardware; measured with calibrate.py, see csr5_sigma_auto).
-constexpr int RULE_R = 8, RULE_S = 16, RULE_T = 256, RULE_U = 16;
-// A matrix with fewer tiles than this at sigma > r gets sigma = r: the chip holds
-// 256 CUs x 16 wavefronts of this kernel, and below about four rounds of them the
-// ramp-up and the last partial round dominate.
+// hardware; measured with calibrate.py, see csr5_sigma_auto).  On this GPU the
+// best sigma does not depend on nnz/row at all for matrices that fill the chip
+// (16 wins by 2-3 % from 1 to 256 nonzeros per row), so r = s = u.
+constexpr int RULE_R = 16, RULE_S = 16, RULE_T = 256, RULE_U = 16;
+// What does matter is the number of tiles: the chip holds 256 CUs x 16
+// wavefronts of this kernel, and below about four rounds of them the ramp-up and
+// the last partial round dominate; such a matrix gets the smaller tile.
 constexpr int64_t RULE_MIN_TILES = 4 * 256 * 16;
+constexpr int RULE_SIGMA_SMALL = 8;
 
 inline int ceil_log2_host(int64_t v) {
     int b = 0;
@@ -705,32 +708,36 @@ __global__ void __launch_bounds__(256)
 k_spmv_fixup(int m, int ntiles, const int32_t* __restrict__ row_ptr,
              const uint32_t* __restrict__ tile_ptr, const double* __restrict__ carry,
              double* __restrict__ y, const uint32_t* __restrict__ status) {
-    const uint32_t st = *status;
-    if (st & BAD_BITS) return;
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = lane_id();
+    const int t0 = gid - lane;                            // first tile of this wavefront
+    const bool live = gid < ntiles;
+    // Everything that does not depend on other loads is requested at once: the
+    // kernel is a chain of memory round trips and nothing else.
+    const uint32_t st = *status;
+    const uint32_t R = live ? (tile_ptr[gid] & ROWMASK) : (0xfffffff0u - uint32_t(lane));
+    double cs = live ? carry[gid] : 0.0;
+    const uint32_t r_after = (gid + 1 < ntiles) ? (tile_ptr[gid + 1] & ROWMASK) : 0xffffffffu;
+    const uint32_t r_before = (t0 > 0 && t0 < ntiles) ? (tile_ptr[t0 - 1] & ROWMASK) : 0xffffffffu;
+    if (st & BAD_BITS) return;
     if (st & CSR5_STATUS_HAS_EMPTY_ROWS) {
         const int64_t stride = int64_t(gridDim.x) * blockDim.x;
         for (int64_t r = gid; r < int64_t(m); r += stride)
             if (row_ptr[r] == row_ptr[r + 1]) y[r] = 0.0;
     }
-    const int t0 = gid - lane;                            // first tile of this wavefront
     if (t0 >= ntiles) return;
-    const bool live = gid < ntiles;
-    uint32_t R = live ? (tile_ptr[gid] & ROWMASK) : (0xfffffff0u - uint32_t(lane));
-    double cs = live ? carry[gid] : 0.0;
 #pragma unroll
     for (int d = 1; d < OMEGA; d <<= 1) {
         double up = __shfl_up(cs, d, OMEGA);
         uint32_t rup = __shfl_up(R, d, OMEGA);
         if (lane >= d && rup == R) cs += up;
     }
-    uint32_t rnext = __shfl_down(R, 1, OMEGA);
-    uint32_t rfirst = __shfl(R, 0, OMEGA);
-    bool run_end = live && ((lane == OMEGA - 1) || (rnext != R));
+    const uint32_t rnext = __shfl_down(R, 1, OMEGA);
+    const uint32_t rfirst = __shfl(R, 0, OMEGA);
+    const bool run_end = live && ((lane == OMEGA - 1) || (rnext != R));
     if (run_end && cs != 0.0 && R < uint32_t(m)) {
-        bool ext_left = (rfirst == R) && t0 > 0 && ((tile_ptr[t0 - 1] & ROWMASK) == R);
-        bool ext_right = (lane == OMEGA - 1) && (gid + 1 < ntiles) && ((tile_ptr[gid + 1] & ROWMASK) == R);
+        const bool ext_left = (rfirst == R) && (r_before == R);
+        const bool ext_right = (lane == OMEGA - 1) && (r_after == R);
         if (ext_left || ext_right) atomic_add_f64(&y[R], cs);
         else y[R] += cs;
     }
@@ -869,7 +876,7 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m) {
     int64_t q = nnz / m;
     if (q > RULE_T) return RULE_U;
     int32_t sigma = q <= RULE_R ? RULE_R : (q <= RULE_S ? int32_t(q) : RULE_S);
-    if (sigma > RULE_R && nnz < RULE_MIN_TILES * OMEGA * sigma) sigma = RULE_R;
+    if (sigma > RULE_SIGMA_SMALL && nnz < RULE_MIN_TILES * OMEGA * sigma) sigma = RULE_SIGMA_SMALL;
     return sigma;
 }
 

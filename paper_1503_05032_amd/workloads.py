@@ -176,14 +176,55 @@ def _zipf_distinct_row(rng, target, n, a_col):
     return head.astype(np.int32)
 
 
-def powerlaw(m=2_000_000, a_len=2.0, a_col=1.5, max_len=200_000, long_above=1000, seed=2) -> Csr:
-    """Square power-law matrix.  Row length target = clip(Zipf(a_len), 1, max_len).
-    Columns are preferential toward low ids: (Zipf(a_col) - 1) mod n, duplicates
-    inside a row dropped (so short rows end up a little shorter than their
-    target).  A row whose target exceeds `long_above` would need an astronomical
-    number of draws to collect that many distinct Zipf values, so it is drawn
-    directly as the distinct set such draws produce (_zipf_distinct_row), with
-    the expected length equal to the target.  Values and x ~ U[0, 1]."""
+def _first_distinct(rng, targets, n, a_col):
+    """For every row r: the first targets[r] DISTINCT values of a stream of
+    (Zipf(a_col) - 1) mod n draws ("draw until the row has its length").
+    Vectorised: draw a batch per row, keep first occurrences in draw order, repeat
+    for the rows that are still short.  Returns (lens, cols), cols sorted inside
+    each row."""
+    m = targets.shape[0]
+    nn = np.int64(n)
+    have = np.empty(0, dtype=np.int64)               # accepted keys row*n + col
+    need = targets.copy()
+    for it in range(200):
+        todo = np.nonzero(need > 0)[0]
+        if todo.size == 0:
+            break
+        nd = need[todo]
+        draws = np.where((it == 0) & (nd == 1), 1, np.ceil(1.7 * nd).astype(np.int64) + 2 + 2 * it)
+        rows = np.repeat(todo, draws)
+        new = rows * nn + (rng.zipf(a_col, size=rows.shape[0]) - 1) % n
+        if have.size:
+            mask = np.zeros(m, dtype=bool)
+            mask[todo] = True
+            ex = have[mask[have // nn]]              # what the unfinished rows already hold
+        else:
+            ex = have
+        cand = np.concatenate([ex, new])
+        uniq, first = np.unique(cand, return_index=True)
+        fresh = first >= ex.shape[0]                 # values the row did not have yet
+        uniq, first = uniq[fresh], first[fresh]
+        urow = uniq // nn
+        order = np.lexsort((first, urow))            # by row, then by draw order
+        uniq, urow = uniq[order], urow[order]
+        start = np.searchsorted(urow, urow, side="left")
+        rank = np.arange(urow.shape[0]) - start
+        acc = uniq[rank < need[urow]]
+        have = np.concatenate([have, acc])
+        need = need - np.bincount(acc // nn, minlength=m)
+    have.sort()
+    r = have // nn
+    c = have - r * nn
+    return np.bincount(r, minlength=m).astype(np.int64), c.astype(np.int32)
+
+
+def powerlaw(m=2_000_000, a_len=2.0, a_col=1.5, max_len=200_000, long_above=256, seed=2) -> Csr:
+    """Square power-law matrix.  Row length = clip(Zipf(a_len), 1, max_len) (mean
+    about 8).  Columns are preferential toward low ids: the row's entries are the
+    first `length` distinct values of a stream of (Zipf(a_col) - 1) mod n draws,
+    sorted.  A row longer than `long_above` would need an astronomical number of
+    draws, so it is drawn directly as the distinct set such a stream converges to
+    (_zipf_distinct_row: expected length = the target).  Values and x ~ U[0, 1]."""
     rng = np.random.default_rng(seed)
     n = m
     max_len = min(max_len, n)
@@ -191,10 +232,7 @@ def powerlaw(m=2_000_000, a_len=2.0, a_col=1.5, max_len=200_000, long_above=1000
     long_rows = np.nonzero(target > long_above)[0]
     short_t = target.copy()
     short_t[long_rows] = 0
-    rows = np.repeat(np.arange(m, dtype=np.int64), short_t)
-    cols = (rng.zipf(a_col, size=rows.shape[0]) - 1) % n
-    lens, c = _dedupe_sorted(rows, cols, m, n)
-    del rows, cols
+    lens, c = _first_distinct(rng, short_t, n, a_col)
     if long_rows.size:
         start = np.zeros(m + 1, dtype=np.int64)
         np.cumsum(lens, out=start[1:])

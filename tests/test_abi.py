@@ -34,20 +34,19 @@ def test_sigma_rule_matches_paper_shape(lib):
     # The library's rule is the four-way map of Section 3.2 with its own constants.
     # Recover them from its behaviour on a matrix large enough that the
     # small-matrix clamp is inactive, and compare with the oracle's rule.
-    m = 4_000_000
-    vals = [B.csr5_sigma_auto(q * m, m) for q in range(0, 400)]
-    r = vals[0]
-    s = max(vals)
-    t = max(q for q in range(400) if vals[q] == s and all(v == s for v in vals[s:q + 1]))
-    u = vals[399]
-    for q in range(0, 400):
-        assert vals[q] == oracle.sigma_rule(q * m, m, r, s, t, u), q
+    m = 40_000_000
+    vals = [B.csr5_sigma_auto(q * m, m) for q in range(1, 400)]
+    r, s, u = vals[0], max(vals), vals[-1]
+    t = 256
+    for q in range(1, 400):
+        assert vals[q - 1] == oracle.sigma_rule(q * m, m, r, s, t, u), q
     assert B.csr5_sigma_auto(0, 0) == r
     assert all(B.CSR5_SIGMA_MIN <= v <= B.CSR5_SIGMA_MAX for v in vals)
-    # small-matrix clamp: fewer than 16384 tiles at sigma > r  ->  r  (only below t)
-    assert B.csr5_sigma_auto(12 * 1000, 1000) == r
-    assert B.csr5_sigma_auto(16384 * 64 * 12, 16384 * 64) == 12
-    assert B.csr5_sigma_auto(16384 * 64 * 12 - 12, 16384 * 64 - 1) == r
+    # small-matrix clamp: fewer than 16384 tiles  ->  sigma 8  (only up to t nonzeros per row)
+    assert B.csr5_sigma_auto(12 * 1000, 1000) == 8
+    big = 16384 * 64 * r
+    assert B.csr5_sigma_auto(big, big // 12) == r
+    assert B.csr5_sigma_auto(big - 1, big // 12) == 8
     assert B.csr5_sigma_auto(1000 * 1000, 1000) == u
 
 
