@@ -260,7 +260,7 @@ def main():
 # keyed by (workload, sigma).  profiles/k_spmv_hbm_traffic_pmc.md has the runs.
 MEASURED_TRAFFIC: dict = {
     (2, 16): int((2.000 * 164521.5 + 8014.8) * 1024),     # stencil: 336.9 MB read + 8.2 MB written
-    (3, 6): int((2.000 * 159411.0 + 16100.0) * 1024),     # power-law
+    (3, 16): int((2.000 * 183718.9 + 15965.8) * 1024),    # power-law: 376.3 MB read + 16.3 MB written
 }
 
 
