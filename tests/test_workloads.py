@@ -1,0 +1,90 @@
+"""CPU checks of the seeded input generators: structure (sorted distinct columns,
+index ranges), the shape statistics the design doc quotes, and reproducibility."""
+import hashlib
+
+import numpy as np
+import pytest
+
+from paper_1503_05032_amd import workloads as wl
+
+
+def check_structure(a):
+    assert a.row_ptr.dtype == np.int32 and a.col_idx.dtype == np.int32 and a.val.dtype == np.float64
+    assert a.row_ptr.shape == (a.m + 1,) and a.row_ptr[0] == 0 and a.row_ptr[-1] == a.nnz
+    lens = np.diff(a.row_ptr.astype(np.int64))
+    assert np.all(lens >= 0)
+    assert a.col_idx.shape == (a.nnz,) and a.val.shape == (a.nnz,) and a.x.shape == (a.n,)
+    if a.nnz:
+        assert a.col_idx.min() >= 0 and a.col_idx.max() < a.n
+        inc = np.diff(a.col_idx.astype(np.int64)) > 0
+        starts = np.zeros(a.nnz, dtype=bool)
+        starts[a.row_ptr[:-1][lens > 0]] = True
+        assert np.all(inc | starts[1:]), "columns must be sorted and distinct inside every row"
+    assert np.all(np.isfinite(a.val)) and np.all(np.isfinite(a.x))
+
+
+def digest(a):
+    h = hashlib.sha256()
+    for arr in (a.row_ptr, a.col_idx, a.val, a.x):
+        h.update(np.ascontiguousarray(arr).tobytes())
+    return h.hexdigest()
+
+
+def test_tiny_uniform():
+    a = wl.config(1)
+    check_structure(a)
+    assert (a.m, a.n, a.nnz) == (2000, 2000, 20510)
+    lens = np.diff(a.row_ptr)
+    assert lens.max() == 20 and (lens == 0).sum() == 89
+    assert digest(a) == digest(wl.config(1))
+
+
+def test_stencil_small_and_full_nnz_formula():
+    a = wl.stencil27(g=12, seed=1)
+    check_structure(a)
+    assert a.nnz == (3 * 12 - 2) ** 3
+    lens = np.diff(a.row_ptr)
+    assert lens.min() == 8 and lens.max() == 27
+    # every row holds its diagonal, value 26
+    for r in (0, 5, 700, a.m - 1):
+        seg = slice(a.row_ptr[r], a.row_ptr[r + 1])
+        k = np.nonzero(a.col_idx[seg] == r)[0]
+        assert k.size == 1 and a.val[seg][k[0]] == 26.0
+    off = a.val[a.val != 26.0]
+    assert np.all(np.abs(off + 1.0) <= 0.01)
+    # symmetric pattern
+    rows = np.repeat(np.arange(a.m), lens)
+    fwd = set(zip(rows[:5000].tolist(), a.col_idx[:5000].tolist()))
+    allp = set(zip(rows.tolist(), a.col_idx.tolist()))
+    assert all((c, r) in allp for r, c in fwd)
+
+
+@pytest.mark.parametrize("cfg,scale", [(3, 0.02), (4, 0.02), (5, 0.01)])
+def test_scaled_irregular_workloads(cfg, scale):
+    a = wl.config(cfg, scale=scale)
+    check_structure(a)
+    lens = np.diff(a.row_ptr)
+    if cfg == 3:
+        assert lens.min() >= 1 and 6.0 < lens.mean() < 11.0
+        assert (a.col_idx < 16).mean() > 0.15            # preferential toward low ids
+        assert lens.max() > 1000
+    if cfg == 4:
+        assert 0.27 < (lens == 0).mean() < 0.33
+        assert lens.max() > 1000
+    if cfg == 5:
+        assert lens.min() >= 1 and 12.0 < lens.mean() < 22.0
+    assert digest(a) == digest(wl.config(cfg, scale=scale))
+
+
+def test_edge_case_catalogue():
+    T = 64 * 4
+    cases = wl.edge_cases(T)
+    names = [c.name for c in cases]
+    assert len(set(names)) == len(names)
+    for a in cases:
+        check_structure(a)
+    by = {c.name: c for c in cases}
+    assert by["all_empty"].nnz == 0
+    assert by["one_long_row"].m == 1 and by["one_long_row"].nnz > 3 * T
+    assert by["exact_two_tiles"].nnz == 2 * T
+    assert by["less_than_one_tile"].nnz < T
