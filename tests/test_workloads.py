@@ -1,5 +1,5 @@
 """CPU checks of the seeded input generators: structure (sorted distinct columns,
-index ranges), the shape statistics the design doc quotes, and reproducibility."""
+index ranges), the shape statistics the documentation quotes, and reproducibility."""
 import hashlib
 
 import numpy as np
