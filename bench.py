@@ -28,12 +28,12 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
 
-def bytes_model(a, info, n_ref):
-    """Algorithmic bytes of one SpMV: val + col_idx (12 B per nonzero), packed
+def bytes_model(a, info, n_ref, vb=8):
+    """Algorithmic bytes of one SpMV: val + col_idx (vb + 4 B per nonzero), packed
     descriptors, tile_ptr, empty_offset and its per-tile starts, every
-    referenced x entry once, y written once."""
+    referenced x entry once, y written once.  vb = bytes per value (8 or 4)."""
     W, p, pc, E = info["desc_words_per_lane"], info["p"], info["p_complete"], info["empty_offset_len"]
-    return (12 * a.nnz + 4 * W * 64 * pc + 4 * (p + 1) + 4 * (pc + 1) + 4 * E + 8 * n_ref + 8 * a.m)
+    return ((vb + 4) * a.nnz + 4 * W * 64 * pc + 4 * (p + 1) + 4 * (pc + 1) + 4 * E + vb * n_ref + vb * a.m)
 
 
 def main():
@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: the 27-point stencil)")
     ap.add_argument("--sigma", type=int, default=0, help="tile height, 0 = the library's rule")
+    ap.add_argument("--dtype", choices=["f64", "f32"], default="f64",
+                    help="f64 is the headline; f32 runs the single-precision instantiation")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--quick", action="store_true", help="skip the conversion/cold/batch extras")
@@ -77,7 +79,17 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    f32 = args.dtype == "f32"
+    tdt = torch.float32 if f32 else torch.float64
+    vb = 4 if f32 else 8
+    convert_ex = B.csr5s_convert_ex if f32 else B.csr5_convert_ex
+    spmv_ex = B.csr5s_spmv_ex if f32 else B.csr5_spmv_ex
+    spmv_profile = B.csr5s_spmv_profile if f32 else B.csr5_spmv_profile
+
     a = wl.config(args.workload)
+    if f32:
+        a.val = a.val.astype(np.float32)
+        a.x = a.x.astype(np.float32)
     st = a.stats()
     n_ref = int(np.unique(a.col_idx).size)
     row_ptr = torch.from_numpy(a.row_ptr).to(dev)
@@ -86,7 +98,7 @@ def main():
     col = col0.clone()
     val = val0.clone()
     x = torch.from_numpy(a.x).to(dev)
-    y = torch.empty(a.m, dtype=torch.float64, device=dev)
+    y = torch.empty(a.m, dtype=tdt, device=dev)
 
     sigma = args.sigma or B.csr5_sigma_auto(a.nnz, a.m)
     ws = torch.empty(B.csr5_workspace_bytes(a.m, a.nnz, sigma), dtype=torch.uint8, device=dev)
@@ -106,8 +118,8 @@ def main():
         torch.cuda.synchronize()
         e0, e1 = ev(), ev()
         e0.record()
-        h = B.csr5_convert_ex(a.m, a.n, a.nnz, row_ptr, col, val, sigma=sigma, workspace=ws,
-                              flags=B.CSR5_FLAG_NO_HOST_CHECK)
+        h = convert_ex(a.m, a.n, a.nnz, row_ptr, col, val, sigma=sigma, workspace=ws,
+                       flags=B.CSR5_FLAG_NO_HOST_CHECK)
         e1.record()
         torch.cuda.synchronize()
         conv_ms.append(e0.elapsed_time(e1))
@@ -116,7 +128,7 @@ def main():
             c2, v2 = col0.clone(), val0.clone()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            h2 = B.csr5_convert_ex(a.m, a.n, a.nnz, row_ptr, c2, v2, sigma=sigma)
+            h2 = convert_ex(a.m, a.n, a.nnz, row_ptr, c2, v2, sigma=sigma)
             torch.cuda.synchronize()
             conv_alloc_ms.append((time.perf_counter() - t0) * 1e3)
             B.csr5_free(h2)
@@ -127,28 +139,28 @@ def main():
 
     # ---------------------------------------------------------------- correctness of this configuration
     import oracle
-    B.csr5_spmv_ex(h, x, y)
+    spmv_ex(h, x, y)
     torch.cuda.synchronize()
-    y_ref, s_abs = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
-    err = np.abs(y.cpu().numpy() - y_ref)
-    parity_ok = bool(np.all(err <= 1e-12 * s_abs + 1e-300))
+    y_ref, s_abs = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val.astype(np.float64), a.x.astype(np.float64))
+    err = np.abs(y.cpu().numpy().astype(np.float64) - y_ref)
+    parity_ok = bool(np.all(err <= (1e-5 if f32 else 1e-12) * s_abs + (1e-30 if f32 else 1e-300)))
 
     # ---------------------------------------------------------------- timed region: exactly K steps
     for _ in range(args.warmup):
-        B.csr5_spmv_ex(h, x, y)
+        spmv_ex(h, x, y)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0, e1 = ev(), ev()
     e0.record()
     for _ in range(args.steps):
-        B.csr5_spmv_ex(h, x, y)
+        spmv_ex(h, x, y)
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = e0.elapsed_time(e1) / args.steps
     gflops = 2.0 * a.nnz / (ms_per_step * 1e-3) / 1e9
-    B_model = bytes_model(a, info, n_ref)
-    B_gather = B_model - 8 * n_ref + 8 * a.nnz
+    B_model = bytes_model(a, info, n_ref, vb)
+    B_gather = B_model - vb * n_ref + vb * a.nnz
 
     extras = {}
     if not args.quick:
@@ -158,7 +170,7 @@ def main():
             e0, e1 = ev(), ev()
             e0.record()
             for _ in range(100):
-                B.csr5_spmv_ex(h, x, y)
+                spmv_ex(h, x, y)
             e1.record()
             torch.cuda.synchronize()
             best = min(best, e0.elapsed_time(e1) / 100)
@@ -170,7 +182,7 @@ def main():
             flush.add_(1.0)
             e0, e1 = ev(), ev()
             e0.record()
-            B.csr5_spmv_ex(h, x, y)
+            spmv_ex(h, x, y)
             e1.record()
             torch.cuda.synchronize()
             cold.append(e0.elapsed_time(e1))
@@ -178,7 +190,7 @@ def main():
         extras["ms_cold_median"] = round(float(np.median(cold)), 5)
 
     # ---------------------------------------------------------------- dominant kernel, HIP events inside the library
-    ms_tiles, ms_fixup = B.csr5_spmv_profile(h, x, y, reps=min(max(args.steps, 50), 2000))
+    ms_tiles, ms_fixup = spmv_profile(h, x, y, reps=min(max(args.steps, 50), 2000))
     achieved = B_model / (ms_tiles * 1e-3) / 1e9
 
     conv = float(np.median(conv_ms))
@@ -193,7 +205,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f64",
+        "dtype": args.dtype,
         "data": "synthetic",
         "config": {
             "workload": f"configs[{args.workload - 1}] {a.name}: {a.m}x{a.n}, nnz={a.nnz}, "
@@ -226,7 +238,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC.get((args.workload, info["sigma"])),
+            "traffic": None if f32 else MEASURED_TRAFFIC.get((args.workload, info["sigma"])),
             "kernel_ms": round(ms_tiles, 5),
             "fixup_kernel_ms": round(ms_fixup, 5),
             "bytes_per_launch": B_model,
@@ -239,7 +251,7 @@ def main():
         reps, t_acc = 0, 0.0
         while t_acc < args.cpu_seconds and reps < 2000:
             t0 = time.perf_counter()
-            oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
+            oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)      # the oracle computes in fp64
             t_acc += time.perf_counter() - t0
             reps += 1
         out["cpu_baseline"] = {

@@ -38,6 +38,10 @@ enum {
     CSR5_ERANGE = -4  /* sigma outside [CSR5_SIGMA_MIN, CSR5_SIGMA_MAX] */
 };
 
+/* value types: the csr5_ entry points take double, the csr5s_ ones float */
+#define CSR5_DTYPE_F64 0
+#define CSR5_DTYPE_F32 1
+
 #define CSR5_OMEGA 64
 #define CSR5_SIGMA_MIN 1
 #define CSR5_SIGMA_MAX 48
@@ -121,6 +125,21 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, i
  */
 int csr5_spmv(csr5_handle_t h, const double *x, double *y);
 int csr5_spmv_ex(csr5_handle_t h, const double *x, double *y, void *hip_stream);
+
+/*
+ * Single-precision variant (the paper's Figure 3 is single precision): same
+ * format, same kernels instantiated for float.  val, x and y are float arrays;
+ * a handle made by csr5s_convert_ex is accepted by csr5s_spmv_ex,
+ * csr5s_spmv_profile, csr5_to_csr and all the introspection calls, and refused
+ * (CSR5_EINVAL) by the double-precision SpMV calls, and vice versa.  Everything
+ * said above about arguments, ownership and errors applies.
+ */
+int csr5s_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, int32_t *col_idx,
+                     float *val, int32_t sigma, void *workspace, size_t workspace_bytes,
+                     void *hip_stream, uint32_t flags, csr5_handle_t *out);
+int csr5s_spmv_ex(csr5_handle_t h, const float *x, float *y, void *hip_stream);
+int csr5s_spmv_profile(csr5_handle_t h, const float *x, float *y, void *hip_stream, int reps,
+                       float *ms);
 
 /*
  * Measurement helper: runs the SpMV `reps` times on the stream with HIP events

@@ -30,6 +30,7 @@ SYMBOLS = [
     "csr5_sigma_auto", "csr5_workspace_bytes", "csr5_convert", "csr5_convert_ex", "csr5_spmv",
     "csr5_spmv_ex", "csr5_spmv_profile", "csr5_to_csr", "csr5_free", "csr5_status", "csr5_get_info", "csr5_get_arrays",
     "csr5_read_array", "csr5_strerror", "csr5_baseline_csr_scalar", "csr5_baseline_csr_vector",
+    "csr5s_convert_ex", "csr5s_spmv_ex", "csr5s_spmv_profile",
 ]
 
 
@@ -62,6 +63,12 @@ def load():
     lib.csr5_convert.argtypes = [i32, i32, i32, vp, vp, vp, C.POINTER(vp)]
     lib.csr5_convert_ex.restype = C.c_int
     lib.csr5_convert_ex.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, sz, vp, u32, C.POINTER(vp)]
+    lib.csr5s_convert_ex.restype = C.c_int
+    lib.csr5s_convert_ex.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, sz, vp, u32, C.POINTER(vp)]
+    lib.csr5s_spmv_ex.restype = C.c_int
+    lib.csr5s_spmv_ex.argtypes = [vp, vp, vp, vp]
+    lib.csr5s_spmv_profile.restype = C.c_int
+    lib.csr5s_spmv_profile.argtypes = [vp, vp, vp, vp, C.c_int, C.POINTER(C.c_float)]
     lib.csr5_spmv.restype = C.c_int
     lib.csr5_spmv.argtypes = [vp, vp, vp]
     lib.csr5_spmv_ex.restype = C.c_int
@@ -145,6 +152,28 @@ def csr5_convert_ex(m, n, nnz, row_ptr, col_idx, val, sigma=0, workspace=None, s
                                 _ptr(workspace), wsb, _stream(stream), int(flags), C.byref(h))
     _chk(rc, "csr5_convert_ex", check)
     return h.value if check else (rc, h.value)
+
+
+def csr5s_convert_ex(m, n, nnz, row_ptr, col_idx, val, sigma=0, workspace=None, stream=None,
+                     flags=CSR5_FLAG_NONE, check=True):
+    """Single precision: `val` is a float32 GPU tensor."""
+    h = C.c_void_p()
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().csr5s_convert_ex(m, n, nnz, _ptr(row_ptr), _ptr(col_idx), _ptr(val), int(sigma),
+                                 _ptr(workspace), wsb, _stream(stream), int(flags), C.byref(h))
+    _chk(rc, "csr5s_convert_ex", check)
+    return h.value if check else (rc, h.value)
+
+
+def csr5s_spmv_ex(h, x, y, stream=None, check=True):
+    return _chk(load().csr5s_spmv_ex(h, _ptr(x), _ptr(y), _stream(stream)), "csr5s_spmv_ex", check)
+
+
+def csr5s_spmv_profile(h, x, y, reps, stream=None):
+    ms = (C.c_float * 2)()
+    _chk(load().csr5s_spmv_profile(h, _ptr(x), _ptr(y), _stream(stream), int(reps), ms),
+         "csr5s_spmv_profile", True)
+    return float(ms[0]), float(ms[1])
 
 
 def csr5_spmv(h, x, y, check=True):

@@ -78,7 +78,7 @@ def sweep(a, sigmas, reps=100):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--sigmas", default="4..48")
-    ap.add_argument("--workloads", default="1,2,3,4,5,probes")
+    ap.add_argument("--workloads", default="1,2,3,4,5,6,probes")
     ap.add_argument("--reps", type=int, default=100)
     ap.add_argument("--json", default=None, help="also write the raw timings here")
     args = ap.parse_args()

@@ -88,8 +88,9 @@ __device__ __forceinline__ int count_le_tileptr(const uint32_t* a, int len, uint
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (OMEGA - 1); }
 
-// Native global fp64 atomic add, no return value.
-__device__ __forceinline__ void atomic_add_f64(double* addr, double v) {
+// Native global floating-point atomic add (fp64 or fp32), no return value.
+template <typename VT>
+__device__ __forceinline__ void atomic_add_fp(VT* addr, VT v) {
     __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -325,9 +326,9 @@ __device__ __forceinline__ void wave_sync_lds() {
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int SIGMA, bool BACK>
+template <int SIGMA, bool BACK, typename VT>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
-k_transpose(int pc, int n, int nnz, int32_t* __restrict__ col_idx, double* __restrict__ val,
+k_transpose(int pc, int n, int nnz, int32_t* __restrict__ col_idx, VT* __restrict__ val,
             uint32_t* __restrict__ status) {
     constexpr int T = OMEGA * SIGMA;
     constexpr int PITCH = TransposeShape<SIGMA>::PITCH;
@@ -337,12 +338,12 @@ k_transpose(int pc, int n, int nnz, int32_t* __restrict__ col_idx, double* __res
     const int tile = blockIdx.x * WAVES + wave;
     const bool active = tile < pc;                 // uniform per wavefront
     const size_t base = size_t(active ? tile : 0) * T;
-    double* buf = lds[wave];
-    int32_t* ibuf = reinterpret_cast<int32_t*>(buf);
+    VT* buf = reinterpret_cast<VT*>(lds[wave]);
+    int32_t* ibuf = reinterpret_cast<int32_t*>(lds[wave]);
     bool bad = false;
 
     // ---- val: HBM -> registers -> LDS -> registers -> HBM
-    double v[SIGMA];
+    VT v[SIGMA];
     if (active) {
 #pragma unroll
         for (int k = 0; k < SIGMA; k++) v[k] = __builtin_nontemporal_load(&val[base + k * OMEGA + lane]);
@@ -464,17 +465,18 @@ constexpr int TAIL_MAX_CHUNKS = (CSR5_SIGMA_MAX * OMEGA) / OMEGA + 1;   // 64-en
 // slot of the chunk it starts in (at most one row starts in a chunk and leaves
 // it), and stored at the end.  The part of a row that began in the complete
 // tiles goes to carry[pc] like a tile's segment 0.
+template <typename VT>
 __device__ void spmv_tail(int m, int nnz, int first, uint32_t tile_ptr_last,
                           const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-                          const double* __restrict__ val, const double* __restrict__ x,
-                          double* __restrict__ y, double* __restrict__ carry_slot) {
-    __shared__ double acc[TAIL_MAX_CHUNKS];
+                          const VT* __restrict__ val, const VT* __restrict__ x,
+                          VT* __restrict__ y, VT* __restrict__ carry_slot) {
+    __shared__ VT acc[TAIL_MAX_CHUNKS];
     __shared__ int acc_row[TAIL_MAX_CHUNKS];
-    __shared__ double acc_first;
+    __shared__ VT acc_first;
     const int lane = lane_id();
     const int wave = threadIdx.x / OMEGA, nwaves = blockDim.x / OMEGA;
-    for (int q = threadIdx.x; q < TAIL_MAX_CHUNKS; q += blockDim.x) { acc[q] = 0.0; acc_row[q] = -1; }
-    if (threadIdx.x == 0) acc_first = 0.0;
+    for (int q = threadIdx.x; q < TAIL_MAX_CHUNKS; q += blockDim.x) { acc[q] = VT(0); acc_row[q] = -1; }
+    if (threadIdx.x == 0) acc_first = VT(0);
     __syncthreads();
     int row_lo = int(tile_ptr_last & ROWMASK);
     if (row_lo > m) row_lo = m;
@@ -485,14 +487,14 @@ __device__ void spmv_tail(int m, int nnz, int first, uint32_t tile_ptr_last,
         const int e = chunk_lo + lane;
         const bool live = e < nnz;
         int row = -2 - lane;                         // distinct keys for dead lanes
-        double prod = 0.0;
+        VT prod = VT(0);
         if (live) {
             row = row_lo + count_le_i32(row_ptr + row_lo, m + 1 - row_lo, e) - 1;
             prod = val[e] * x[col_idx[e]];
         }
 #pragma unroll
         for (int d = 1; d < OMEGA; d <<= 1) {
-            double up = __shfl_up(prod, d, OMEGA);
+            VT up = __shfl_up(prod, d, OMEGA);
             int rup = __shfl_up(row, d, OMEGA);
             if (lane >= d && rup == row) prod += up;
         }
@@ -519,14 +521,14 @@ __device__ void spmv_tail(int m, int nnz, int first, uint32_t tile_ptr_last,
     if (threadIdx.x == 0) *carry_slot = acc_first;
 }
 
-template <int SIGMA>
+template <int SIGMA, typename VT>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
 k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
        const int32_t* __restrict__ row_ptr, const uint32_t* __restrict__ tile_ptr,
        const uint32_t* __restrict__ tile_desc, const int32_t* __restrict__ eop,
        const int32_t* __restrict__ eo, const int32_t* __restrict__ col_idx,
-       const double* __restrict__ val, const double* __restrict__ x, double* __restrict__ y,
-       double* __restrict__ carry, const uint32_t* __restrict__ status) {
+       const VT* __restrict__ val, const VT* __restrict__ x, VT* __restrict__ y,
+       VT* __restrict__ carry, const uint32_t* __restrict__ status) {
     constexpr int T = OMEGA * SIGMA;
     constexpr int YBITS = 32 - __builtin_clz(uint32_t(T - 1));        // ceil(log2(64*sigma))
     constexpr int W = (SIGMA + SBITS + YBITS + 31) / 32;
@@ -562,7 +564,7 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
         const int e4 = q * OMEGA + lane;                  // index of the int4 inside the tile
         c4[q] = (SIGMA % 4 == 0 || e4 < T / 4) ? __builtin_nontemporal_load(&col4[e4]) : i32x4{0, 0, 0, 0};
     }
-    double v[SIGMA];
+    VT v[SIGMA];
 #pragma unroll
     for (int j = 0; j < SIGMA; j++) v[j] = __builtin_nontemporal_load(&val[tile_base + j * OMEGA + lane]);
 
@@ -600,9 +602,9 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     // that lane L holds CSR entries k*64+L (64 consecutive entries per gather
     // instruction: few distinct cache lines), x is gathered in that order, and
     // the values return through the same LDS buffer to the owner lanes.
-    double* const xb = lds[wave];
-    int32_t* const cb = reinterpret_cast<int32_t*>(xb);
-    double xv[SIGMA];
+    VT* const xb = reinterpret_cast<VT*>(lds[wave]);
+    int32_t* const cb = reinterpret_cast<int32_t*>(lds[wave]);
+    VT xv[SIGMA];
     {
 #pragma unroll
         for (int q = 0; q < NC4; q++) {
@@ -639,8 +641,8 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     // ---- per-column walk.  Finished segment sums are parked in LDS (the buffer
     // is free again), slot = segment number inside the tile, and written to y
     // afterwards, 64 consecutive segments per store instruction.
-    double* const yb = xb;                                // T <= 64*PITCH slots
-    double sum = 0.0, red = 0.0;
+    VT* const yb = xb;                                // T <= 64*PITCH slots
+    VT sum = VT(0), red = VT(0);
     bool seen = false;
     uint32_t seg = yo;
 #pragma unroll
@@ -653,22 +655,22 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
                 red = sum;
                 seen = true;
             }
-            sum = 0.0;
+            sum = VT(0);
         }
         sum = fma(v[j], xv[j], sum);
     }
-    double blue = sum;
-    if (!seen) { red = sum; blue = 0.0; }                 // whole column is red
+    VT blue = sum;
+    if (!seen) { red = sum; blue = VT(0); }                 // whole column is red
 
     // ---- in-tile segmented sum of the red partials
     uint64_t heads = __ballot(seen);                      // bit 0 is always set
-    double tmp = __shfl_down(red, 1, OMEGA);
-    if (lane == OMEGA - 1) tmp = 0.0;
+    VT tmp = __shfl_down(red, 1, OMEGA);
+    if (lane == OMEGA - 1) tmp = VT(0);
     uint64_t right = (lane == OMEGA - 1) ? 0ull : (heads >> (lane + 1));
     int end = right ? (lane + __builtin_ctzll(right)) : (OMEGA - 1);   // last lane of my segment
 #pragma unroll
     for (int d = 1; d < OMEGA; d <<= 1) {
-        double dn = __shfl_down(tmp, d, OMEGA);
+        VT dn = __shfl_down(tmp, d, OMEGA);
         if (lane + d <= end) tmp += dn;
     }
     if (seen && seg < uint32_t(T)) yb[seg] = blue + tmp;
@@ -684,9 +686,9 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     for (uint32_t s0 = 0; s0 < nseg; s0 += OMEGA) {
         const uint32_t sg = s0 + lane;
         if (sg < nseg) {
-            const double value = yb[sg];
+            const VT value = yb[sg];
             const uint32_t row = row0 + (dirty ? uint32_t(eo_t[sg]) : sg);
-            if (sg == 0) carry[tile] = cont0 ? value : 0.0;
+            if (sg == 0) carry[tile] = cont0 ? value : VT(0);
             if ((sg != 0 || !cont0) && row < uint32_t(m)) y[row] = value;
         }
     }
@@ -704,10 +706,11 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
 // Rows without nonzeros are stored by no tile; they get their 0 here when the
 // matrix has any (status bit set during conversion).
 // ----------------------------------------------------------------------------
+template <typename VT>
 __global__ void __launch_bounds__(256)
 k_spmv_fixup(int m, int ntiles, const int32_t* __restrict__ row_ptr,
-             const uint32_t* __restrict__ tile_ptr, const double* __restrict__ carry,
-             double* __restrict__ y, const uint32_t* __restrict__ status) {
+             const uint32_t* __restrict__ tile_ptr, const VT* __restrict__ carry,
+             VT* __restrict__ y, const uint32_t* __restrict__ status) {
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = lane_id();
     const int t0 = gid - lane;                            // first tile of this wavefront
@@ -716,56 +719,56 @@ k_spmv_fixup(int m, int ntiles, const int32_t* __restrict__ row_ptr,
     // kernel is a chain of memory round trips and nothing else.
     const uint32_t st = *status;
     const uint32_t R = live ? (tile_ptr[gid] & ROWMASK) : (0xfffffff0u - uint32_t(lane));
-    double cs = live ? carry[gid] : 0.0;
+    VT cs = live ? carry[gid] : VT(0);
     const uint32_t r_after = (gid + 1 < ntiles) ? (tile_ptr[gid + 1] & ROWMASK) : 0xffffffffu;
     const uint32_t r_before = (t0 > 0 && t0 < ntiles) ? (tile_ptr[t0 - 1] & ROWMASK) : 0xffffffffu;
     if (st & BAD_BITS) return;
     if (st & CSR5_STATUS_HAS_EMPTY_ROWS) {
         const int64_t stride = int64_t(gridDim.x) * blockDim.x;
         for (int64_t r = gid; r < int64_t(m); r += stride)
-            if (row_ptr[r] == row_ptr[r + 1]) y[r] = 0.0;
+            if (row_ptr[r] == row_ptr[r + 1]) y[r] = VT(0);
     }
     if (t0 >= ntiles) return;
 #pragma unroll
     for (int d = 1; d < OMEGA; d <<= 1) {
-        double up = __shfl_up(cs, d, OMEGA);
+        VT up = __shfl_up(cs, d, OMEGA);
         uint32_t rup = __shfl_up(R, d, OMEGA);
         if (lane >= d && rup == R) cs += up;
     }
     const uint32_t rnext = __shfl_down(R, 1, OMEGA);
     const uint32_t rfirst = __shfl(R, 0, OMEGA);
     const bool run_end = live && ((lane == OMEGA - 1) || (rnext != R));
-    if (run_end && cs != 0.0 && R < uint32_t(m)) {
+    if (run_end && cs != VT(0) && R < uint32_t(m)) {
         const bool ext_left = (rfirst == R) && (r_before == R);
         const bool ext_right = (lane == OMEGA - 1) && (r_after == R);
-        if (ext_left || ext_right) atomic_add_f64(&y[R], cs);
+        if (ext_left || ext_right) atomic_add_fp(&y[R], cs);
         else y[R] += cs;
     }
 }
 
-template <int SIGMA>
+template <int SIGMA, typename VT>
 hipError_t launch_spmv(const Geom& g, int m, int nnz, const int32_t* row_ptr, const uint32_t* tile_ptr,
                        const uint32_t* tile_desc, const int32_t* eop, const int32_t* eo,
-                       const int32_t* col_idx, const double* val, const double* x, double* y,
-                       double* carry, const uint32_t* status, hipStream_t s) {
+                       const int32_t* col_idx, const VT* val, const VT* x, VT* y,
+                       VT* carry, const uint32_t* status, hipStream_t s) {
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
     uint32_t nb_tiles = uint32_t((g.pc + WAVES - 1) / WAVES);
     uint32_t has_tail = (int64_t(g.pc) * g.T < nnz) ? 1u : 0u;
     uint32_t nb = nb_tiles + has_tail;
     if (nb == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_spmv<SIGMA>, dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, nb_tiles, has_tail,
+    hipLaunchKernelGGL((k_spmv<SIGMA, VT>), dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, nb_tiles, has_tail,
                        row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status);
     return hipGetLastError();
 }
 
-template <int SIGMA, bool BACK>
-hipError_t launch_transpose(const Geom& g, int n, int nnz, int32_t* col_idx, double* val,
+template <int SIGMA, bool BACK, typename VT>
+hipError_t launch_transpose(const Geom& g, int n, int nnz, int32_t* col_idx, VT* val,
                             uint32_t* status, hipStream_t s) {
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
     uint32_t nb = uint32_t((g.pc + WAVES - 1) / WAVES);
     if (nb == 0) nb = BACK ? 0 : 1;   // forward pass still validates the tail's columns
     if (nb == 0) return hipSuccess;
-    hipLaunchKernelGGL((k_transpose<SIGMA, BACK>), dim3(nb), dim3(WAVES * OMEGA), 0, s, g.pc, n, nnz,
+    hipLaunchKernelGGL((k_transpose<SIGMA, BACK, VT>), dim3(nb), dim3(WAVES * OMEGA), 0, s, g.pc, n, nnz,
                        col_idx, val, status);
     return hipGetLastError();
 }
@@ -820,13 +823,14 @@ struct csr5_handle_s {
     Geom g;
     const int32_t* row_ptr;
     int32_t* col_idx;
-    double* val;
+    void* val;             // double* or float*, see dtype
+    int dtype;             // CSR5_DTYPE_F64 / CSR5_DTYPE_F32
     uint32_t* tile_ptr;
     uint32_t* tile_desc;
     int32_t* eop;
     int32_t* eo;
     uint32_t* status;
-    double* carry;         // one slot per tile (incomplete one included): cross-tile sums of an SpMV
+    void* carry;           // one 8-byte slot per tile (incomplete one included): cross-tile sums of an SpMV
     void* owned;           // hipMalloc'ed block, or NULL when a workspace was given
     hipStream_t conv_stream;
     bool in_csr5_order;
@@ -888,16 +892,19 @@ size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma) {
     return make_layout(m, g).total;
 }
 
-int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
-                    double* val, int32_t sigma, void* workspace, size_t workspace_bytes,
-                    void* hip_stream, uint32_t flags, csr5_handle_t* out) {
+}  // extern "C"
+
+template <typename VT>
+static int convert_impl(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
+                        VT* val, int32_t sigma, void* workspace, size_t workspace_bytes,
+                        void* hip_stream, uint32_t flags, csr5_handle_t* out) {
     if (!out) return CSR5_EINVAL;
     *out = nullptr;
     if (m < 0 || n < 0 || nnz < 0) return CSR5_EINVAL;
     if (!row_ptr) return CSR5_EINVAL;                      // row_ptr has m+1 >= 1 entries
     if (nnz > 0 && (!col_idx || !val || m == 0 || n == 0)) return CSR5_EINVAL;
-    // the kernels read col_idx with 16-byte and val with 8-byte accesses
-    if ((reinterpret_cast<uintptr_t>(col_idx) & 15) || (reinterpret_cast<uintptr_t>(val) & 7) ||
+    // the kernels read col_idx with 16-byte accesses and val element-wise
+    if ((reinterpret_cast<uintptr_t>(col_idx) & 15) || (reinterpret_cast<uintptr_t>(val) & (sizeof(VT) - 1)) ||
         (reinterpret_cast<uintptr_t>(row_ptr) & 3)) return CSR5_EINVAL;
     if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
     if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX) return CSR5_ERANGE;
@@ -935,11 +942,12 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, i
     }
     h->m = m; h->n = n; h->nnz = nnz; h->g = g;
     h->row_ptr = row_ptr; h->col_idx = col_idx; h->val = val;
+    h->dtype = std::is_same<VT, float>::value ? CSR5_DTYPE_F32 : CSR5_DTYPE_F64;
     h->tile_ptr = reinterpret_cast<uint32_t*>(basep + L.off_tile_ptr);
     h->tile_desc = reinterpret_cast<uint32_t*>(basep + L.off_desc);
     h->eop = reinterpret_cast<int32_t*>(basep + L.off_eop);
     h->eo = reinterpret_cast<int32_t*>(basep + L.off_eo);
-    h->carry = reinterpret_cast<double*>(basep + L.off_carry);
+    h->carry = basep + L.off_carry;
     h->status = reinterpret_cast<uint32_t*>(basep + L.off_status);
     h->conv_stream = s;
     h->in_csr5_order = true;
@@ -976,7 +984,7 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, i
     }
     if (e == hipSuccess && nnz > 0) {   // step 4
         switch (sigma) {
-#define X(S) case S: e = launch_transpose<S, false>(g, n, nnz, col_idx, val, h->status, s); break;
+#define X(S) case S: e = launch_transpose<S, false, VT>(g, n, nnz, col_idx, val, h->status, s); break;
             CSR5_FOR_SIGMA(X)
 #undef X
             default: e = hipErrorInvalidValue;
@@ -1008,20 +1016,41 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, i
     return CSR5_OK;
 }
 
+extern "C" {
+
+int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
+                    double* val, int32_t sigma, void* workspace, size_t workspace_bytes,
+                    void* hip_stream, uint32_t flags, csr5_handle_t* out) {
+    return convert_impl<double>(m, n, nnz, row_ptr, col_idx, val, sigma, workspace, workspace_bytes,
+                                hip_stream, flags, out);
+}
+
+int csr5s_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
+                     float* val, int32_t sigma, void* workspace, size_t workspace_bytes,
+                     void* hip_stream, uint32_t flags, csr5_handle_t* out) {
+    return convert_impl<float>(m, n, nnz, row_ptr, col_idx, val, sigma, workspace, workspace_bytes,
+                               hip_stream, flags, out);
+}
+
 int csr5_convert(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
                  double* val, csr5_handle_t* out) {
     return csr5_convert_ex(m, n, nnz, row_ptr, col_idx, val, 0, nullptr, 0, nullptr, CSR5_FLAG_NONE, out);
 }
 
+}  // extern "C"
+
 // One SpMV: the tile kernel, then the carry fix-up.  `ev`, when given, points at
 // three events recorded before, between and after the two launches.
-static int spmv_launch(csr5_handle_t h, const double* x, double* y, hipStream_t s, hipEvent_t* ev) {
+template <typename VT>
+static int spmv_launch(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, hipEvent_t* ev) {
     if (ev && hipEventRecord(ev[0], s) != hipSuccess) return CSR5_EHIP;
     hipError_t e = hipSuccess;
+    VT* carry = static_cast<VT*>(h->carry);
     if (h->nnz > 0) {
         switch (h->g.sigma) {
-#define X(S) case S: e = launch_spmv<S>(h->g, h->m, h->nnz, h->row_ptr, h->tile_ptr, h->tile_desc, h->eop, \
-                                        h->eo, h->col_idx, h->val, x, y, h->carry, h->status, s); break;
+#define X(S) case S: e = launch_spmv<S, VT>(h->g, h->m, h->nnz, h->row_ptr, h->tile_ptr, h->tile_desc, h->eop, \
+                                            h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y, carry,  \
+                                            h->status, s); break;
             CSR5_FOR_SIGMA(X)
 #undef X
             default: e = hipErrorInvalidValue;
@@ -1037,25 +1066,28 @@ static int spmv_launch(csr5_handle_t h, const double* x, double* y, hipStream_t 
         if (nb_rows > 512) nb_rows = 512;
         if (nb < nb_rows) nb = nb_rows;
         if (nb == 0) nb = 1;
-        hipLaunchKernelGGL(k_spmv_fixup, dim3(uint32_t(nb)), dim3(256), 0, s, h->m, ntiles, h->row_ptr,
-                           h->tile_ptr, h->carry, y, h->status);
+        hipLaunchKernelGGL(k_spmv_fixup<VT>, dim3(uint32_t(nb)), dim3(256), 0, s, h->m, ntiles, h->row_ptr,
+                           h->tile_ptr, carry, y, h->status);
         if (hipGetLastError() != hipSuccess) return CSR5_EHIP;
     }
     if (ev && hipEventRecord(ev[2], s) != hipSuccess) return CSR5_EHIP;
     return CSR5_OK;
 }
 
-int csr5_spmv_ex(csr5_handle_t h, const double* x, double* y, void* hip_stream) {
-    if (!h || !h->in_csr5_order) return CSR5_EINVAL;
+template <typename VT>
+static int spmv_checked(csr5_handle_t h, const VT* x, VT* y, void* hip_stream) {
+    constexpr int want = std::is_same<VT, float>::value ? CSR5_DTYPE_F32 : CSR5_DTYPE_F64;
+    if (!h || !h->in_csr5_order || h->dtype != want) return CSR5_EINVAL;
     if (h->m > 0 && !y) return CSR5_EINVAL;
     if (h->nnz > 0 && !x) return CSR5_EINVAL;
     if (h->m == 0) return CSR5_OK;
-    return spmv_launch(h, x, y, static_cast<hipStream_t>(hip_stream), nullptr);
+    return spmv_launch<VT>(h, x, y, static_cast<hipStream_t>(hip_stream), nullptr);
 }
 
-int csr5_spmv_profile(csr5_handle_t h, const double* x, double* y, void* hip_stream, int reps,
-                      float* ms) {
-    if (!h || !h->in_csr5_order || !ms || reps <= 0 || reps > 100000) return CSR5_EINVAL;
+template <typename VT>
+static int spmv_profile(csr5_handle_t h, const VT* x, VT* y, void* hip_stream, int reps, float* ms) {
+    constexpr int want = std::is_same<VT, float>::value ? CSR5_DTYPE_F32 : CSR5_DTYPE_F64;
+    if (!h || !h->in_csr5_order || h->dtype != want || !ms || reps <= 0 || reps > 100000) return CSR5_EINVAL;
     if (h->m == 0 || !y || (h->nnz > 0 && !x)) return CSR5_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     size_t nev = size_t(reps) * 3;
@@ -1065,7 +1097,7 @@ int csr5_spmv_profile(csr5_handle_t h, const double* x, double* y, void* hip_str
     size_t made = 0;
     for (; made < nev; made++)
         if (hipEventCreate(&ev[made]) != hipSuccess) { rc = CSR5_EHIP; break; }
-    for (int r = 0; rc == CSR5_OK && r < reps; r++) rc = spmv_launch(h, x, y, s, ev + size_t(r) * 3);
+    for (int r = 0; rc == CSR5_OK && r < reps; r++) rc = spmv_launch<VT>(h, x, y, s, ev + size_t(r) * 3);
     if (hipStreamSynchronize(s) != hipSuccess && rc == CSR5_OK) rc = CSR5_EHIP;
     double acc[2] = {0.0, 0.0};
     for (int r = 0; rc == CSR5_OK && r < reps; r++) {
@@ -1087,7 +1119,21 @@ int csr5_spmv_profile(csr5_handle_t h, const double* x, double* y, void* hip_str
     return rc;
 }
 
-int csr5_spmv(csr5_handle_t h, const double* x, double* y) { return csr5_spmv_ex(h, x, y, nullptr); }
+extern "C" {
+
+int csr5_spmv_ex(csr5_handle_t h, const double* x, double* y, void* hip_stream) {
+    return spmv_checked<double>(h, x, y, hip_stream);
+}
+int csr5_spmv(csr5_handle_t h, const double* x, double* y) { return spmv_checked<double>(h, x, y, nullptr); }
+int csr5s_spmv_ex(csr5_handle_t h, const float* x, float* y, void* hip_stream) {
+    return spmv_checked<float>(h, x, y, hip_stream);
+}
+int csr5_spmv_profile(csr5_handle_t h, const double* x, double* y, void* hip_stream, int reps, float* ms) {
+    return spmv_profile<double>(h, x, y, hip_stream, reps, ms);
+}
+int csr5s_spmv_profile(csr5_handle_t h, const float* x, float* y, void* hip_stream, int reps, float* ms) {
+    return spmv_profile<float>(h, x, y, hip_stream, reps, ms);
+}
 
 int csr5_to_csr(csr5_handle_t h, void* hip_stream) {
     if (!h) return CSR5_EINVAL;
@@ -1096,7 +1142,10 @@ int csr5_to_csr(csr5_handle_t h, void* hip_stream) {
     hipError_t e = hipSuccess;
     if (h->nnz > 0) {
         switch (h->g.sigma) {
-#define X(S) case S: e = launch_transpose<S, true>(h->g, h->n, h->nnz, h->col_idx, h->val, h->status, s); break;
+#define X(S) case S: e = (h->dtype == CSR5_DTYPE_F32)                                                            \
+        ? launch_transpose<S, true, float>(h->g, h->n, h->nnz, h->col_idx, static_cast<float*>(h->val), h->status, s)   \
+        : launch_transpose<S, true, double>(h->g, h->n, h->nnz, h->col_idx, static_cast<double*>(h->val), h->status, s); \
+        break;
             CSR5_FOR_SIGMA(X)
 #undef X
             default: e = hipErrorInvalidValue;

@@ -89,7 +89,7 @@ def measure(a, reps=50, sigma=0):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workloads", default="1,2,3,4,5")
+    ap.add_argument("--workloads", default="1,2,3,4,5,6")
     ap.add_argument("--json", default=None)
     args = ap.parse_args()
     from . import binding as B

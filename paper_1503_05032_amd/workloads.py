@@ -315,11 +315,27 @@ def mixed_large(m=8_000_000, band=5000, p_band=0.8, mu=2.5, sg=1.5, seed=4,
 
 
 # --------------------------------------------------------------------------
+# the one matrix of the paper's suite that is fully specified in its text
+# --------------------------------------------------------------------------
+def dense(n=2000, seed=5) -> Csr:
+    """Dense n x n matrix stored in CSR (Table 2, matrix r1 "Dense": 2K x 2K,
+    4.0 M nonzeros, 2K per row; the only suite matrix that does not come from a
+    collection).  Values and x ~ U[-1, 1]."""
+    rng = np.random.default_rng(seed)
+    lens = np.full(n, n, dtype=np.int64)
+    cols = np.tile(np.arange(n, dtype=np.int32), n)
+    val = rng.uniform(-1.0, 1.0, size=n * n)
+    x = rng.uniform(-1.0, 1.0, size=n)
+    return _finish(n, n, lens, cols, val, x, f"dense_{n}")
+
+
+# --------------------------------------------------------------------------
 # registry of the five headline workloads and their scaled-down versions
 # --------------------------------------------------------------------------
 def config(i: int, scale: float = 1.0) -> Csr:
-    """Workload i in 1..5 at full size (scale=1) or shrunk (scale<1 reduces the
-    number of rows; the per-row distributions are unchanged)."""
+    """Workload i in 1..5 (6 = the paper's dense 2K x 2K matrix) at full size
+    (scale=1) or shrunk (scale<1 reduces the number of rows; the per-row
+    distributions are unchanged)."""
     if i == 1:
         return tiny_uniform()
     if i == 2:
@@ -335,6 +351,8 @@ def config(i: int, scale: float = 1.0) -> Csr:
     if i == 5:
         m = max(20_000, int(8_000_000 * scale))
         return mixed_large(m=m, band=min(5000, m // 4), chunk_rows=1_000_000)
+    if i == 6:                      # extra: the paper's own dense matrix
+        return dense(max(64, int(round(2000 * scale ** 0.5))))
     raise ValueError(i)
 
 

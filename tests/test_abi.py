@@ -22,7 +22,7 @@ def lib():
 
 def test_header_symbols_exported(lib):
     hdr = open(os.path.join(ROOT, "include", "csr5.h")).read()
-    declared = set(re.findall(r"\b(csr5_[a-z_0-9]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(csr5s?_[a-z_0-9]+)\s*\(", hdr))
     declared -= {"csr5_handle_s"}
     assert declared == set(B.SYMBOLS), declared ^ set(B.SYMBOLS)
     raw = ctypes.CDLL(B.LIB_PATH)

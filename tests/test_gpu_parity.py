@@ -70,7 +70,7 @@ def test_config1_auto_sigma_and_plain_convert():
     B.csr5_free(h)
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5, 6])
 def test_full_size_configs(cfg):
     say("generating config", cfg)
     a = wl.config(cfg)
@@ -260,3 +260,60 @@ def test_random_matrices():
         check_format(d, h, (a.name, sigma))
         check_spmv(d, h, (a.name, sigma))
         B.csr5_free(h)
+
+
+# ---------------------------------------------------------------- single precision
+TOL32 = 1e-5      # depth of any addition chain <= sigma + 6 + 6 + a few (<= 64): 64 * 2^-24 = 3.8e-6
+
+
+def _run32(a, sigma):
+    dev = torch.device("cuda:0")
+    val32 = a.val.astype(np.float32)
+    x32 = a.x.astype(np.float32)
+    row_ptr = torch.from_numpy(a.row_ptr).to(dev)
+    col = torch.from_numpy(a.col_idx).to(dev) if a.nnz else torch.zeros(4, dtype=torch.int32, device=dev)
+    val = torch.from_numpy(val32).to(dev) if a.nnz else torch.zeros(4, dtype=torch.float32, device=dev)
+    x = torch.from_numpy(x32).to(dev) if a.n else torch.zeros(1, dtype=torch.float32, device=dev)
+    y = torch.full((max(a.m, 1),), float("nan"), dtype=torch.float32, device=dev)
+    ws = torch.empty(B.csr5_workspace_bytes(a.m, a.nnz, sigma), dtype=torch.uint8, device=dev)
+    h = B.csr5s_convert_ex(a.m, a.n, a.nnz, row_ptr, col, val, sigma=sigma, workspace=ws)
+    info = B.csr5_get_info(h)
+    ref = oracle.convert(a.m, a.n, a.nnz, a.row_ptr, a.col_idx, val32.astype(np.float64), 64, info["sigma"])
+    assert np.array_equal(B.csr5_read_array(h, B.CSR5_ARRAY_TILE_PTR), ref.tile_ptr)
+    assert np.array_equal(B.csr5_read_array(h, B.CSR5_ARRAY_TILE_DESC), ref.tile_desc)
+    assert np.array_equal(B.csr5_read_array(h, B.CSR5_ARRAY_EMPTY_OFFSET_PTR), ref.empty_offset_ptr)
+    assert np.array_equal(B.csr5_read_array(h, B.CSR5_ARRAY_EMPTY_OFFSET), ref.empty_offset)
+    if a.nnz:
+        assert np.array_equal(col.cpu().numpy(), ref.col_idx)
+        assert np.array_equal(val.cpu().numpy().astype(np.float64), ref.val)     # bit-exact in float
+    B.csr5s_spmv_ex(h, x, y)
+    torch.cuda.synchronize()
+    y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, val32.astype(np.float64), x32.astype(np.float64))
+    got = y.cpu().numpy()[:a.m].astype(np.float64)
+    bad = np.nonzero(~(np.abs(got - y_ref) <= TOL32 * s + 1e-30))[0]
+    assert bad.size == 0, (a.name, sigma, int(bad.size), int(bad[0]), got[bad[0]], y_ref[bad[0]], s[bad[0]])
+    assert np.all(got[np.diff(a.row_ptr) == 0] == 0.0)
+    # the double-precision calls refuse a single-precision handle
+    assert B.csr5_spmv_ex(h, x, y, check=False) == B.CSR5_EINVAL
+    B.csr5_to_csr(h)
+    torch.cuda.synchronize()
+    if a.nnz:
+        assert np.array_equal(col.cpu().numpy(), a.col_idx)
+        assert np.array_equal(val.cpu().numpy(), val32)
+    B.csr5_free(h)
+
+
+@pytest.mark.parametrize("sigma", [4, 16, 33, 48])
+def test_single_precision_edge_cases(sigma):
+    for a in wl.edge_cases(64 * sigma):
+        if a.name == "wide_values":
+            continue                      # 16 decades of magnitudes do not fit single precision's range of sums
+        say("f32 edge", sigma, a.name)
+        _run32(a, sigma)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_single_precision_full_size(cfg):
+    a = wl.config(cfg)
+    say("f32", a.stats())
+    _run32(a, 0)

@@ -76,6 +76,13 @@ def test_scaled_irregular_workloads(cfg, scale):
     assert digest(a) == digest(wl.config(cfg, scale=scale))
 
 
+def test_dense_matrix_of_the_paper():
+    a = wl.dense(200)
+    check_structure(a)
+    assert a.nnz == 200 * 200 and np.all(np.diff(a.row_ptr) == 200)
+    assert wl.config(6).nnz == 4_000_000                  # Table 2, r1: 2K x 2K, 4.0M
+
+
 def test_edge_case_catalogue():
     T = 64 * 4
     cases = wl.edge_cases(T)
