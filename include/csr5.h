@@ -84,9 +84,11 @@ size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma);
  *   row_ptr     int32[m+1], row_ptr[0] = 0, row_ptr[m] = nnz, non-decreasing.
  *               BORROWED: read now and again by every csr5_spmv (the format
  *               keeps it unchanged, Section 1); must outlive the handle.
- *   col_idx     int32[nnz], values in [0, n), 16-byte aligned.  MODIFIED IN PLACE: inside every
- *   val         double[nnz].    complete tile the entries go from CSR order to
- *               tile column-major order (Section 3.1).  The caller keeps
+ *   col_idx     int32[nnz], values in [0, n), 16-byte aligned.
+ *   val         double[nnz].
+ *               Both MODIFIED IN PLACE: inside every complete tile the entries
+ *               go from CSR order to tile column-major order (Section 3.1);
+ *               the entries after the last complete tile stay.  The caller keeps
  *               ownership of the memory, must keep it alive for the handle's
  *               lifetime, and gets CSR order back with csr5_to_csr.
  *   out         receives the handle.  The handle owns tile_ptr, tile_desc
