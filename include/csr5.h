@@ -35,7 +35,7 @@ enum {
     CSR5_EINVAL = -1, /* bad argument (null pointer, negative size, inconsistent row_ptr) */
     CSR5_ENOMEM = -2, /* allocation failed or workspace too small */
     CSR5_EHIP = -3,   /* a HIP runtime call or kernel launch failed */
-    CSR5_ERANGE = -4  /* sigma outside [CSR5_SIGMA_MIN, CSR5_SIGMA_MAX] */
+    CSR5_ERANGE = -4  /* sigma outside [CSR5_SIGMA_MIN, CSR5_SIGMA_MAX], or matrix beyond the stated limits */
 };
 
 /* value types: the csr5_ entry points take double, the csr5s_ ones float */
@@ -142,6 +142,28 @@ int csr5s_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, 
 int csr5s_spmv_ex(csr5_handle_t h, const float *x, float *y, void *hip_stream);
 int csr5s_spmv_profile(csr5_handle_t h, const float *x, float *y, void *hip_stream, int reps,
                        float *ms);
+
+/*
+ * 64-bit index variant (Section 3.3 mentions it for tile_ptr: a 63-bit row
+ * index with the top bit as the empty-row flag), for matrices of 2^31 nonzeros
+ * and more: row_ptr is int64[m+1], nnz is int64, and the handle's tile_ptr and
+ * empty_offset_ptr have 8-byte entries (tile_ptr: bit 63 is the flag).  Rows,
+ * columns and the other arrays are as above (m, n < 2^31; col_idx, tile_desc
+ * and empty_offset are 32-bit), values are double.  Limits: at most 2^26 - 5
+ * tiles (one wavefront each; a grid holds fewer than 2^32 threads), which is
+ * 68 G nonzeros at sigma = 16, and m + tiles < 2^32 - 512; beyond them
+ * CSR5_ERANGE (csr5l_workspace_bytes: 0).
+ * The handle is accepted by csr5_spmv, csr5_spmv_ex, csr5_spmv_profile,
+ * csr5_to_csr, csr5_status, csr5_get_info, csr5_read_array (8-byte entries for
+ * arrays 0 and 2) and csr5_free; csr5_get_arrays refuses it, csr5l_get_arrays
+ * refuses a 32-bit one.  Everything else said for csr5_convert_ex applies.
+ */
+size_t csr5l_workspace_bytes(int32_t m, int64_t nnz, int32_t sigma);
+int csr5l_convert_ex(int32_t m, int32_t n, int64_t nnz, const int64_t *row_ptr, int32_t *col_idx,
+                     double *val, int32_t sigma, void *workspace, size_t workspace_bytes,
+                     void *hip_stream, uint32_t flags, csr5_handle_t *out);
+int csr5l_get_arrays(csr5_handle_t h, const uint64_t **tile_ptr, const uint32_t **tile_desc,
+                     const int64_t **empty_offset_ptr, const int32_t **empty_offset);
 
 /*
  * Measurement helper: runs the SpMV `reps` times on the stream with HIP events

@@ -31,6 +31,7 @@ SYMBOLS = [
     "csr5_spmv_ex", "csr5_spmv_profile", "csr5_to_csr", "csr5_free", "csr5_status", "csr5_get_info", "csr5_get_arrays",
     "csr5_read_array", "csr5_strerror", "csr5_baseline_csr_scalar", "csr5_baseline_csr_vector",
     "csr5s_convert_ex", "csr5s_spmv_ex", "csr5s_spmv_profile",
+    "csr5l_workspace_bytes", "csr5l_convert_ex", "csr5l_get_arrays",
 ]
 
 
@@ -65,6 +66,12 @@ def load():
     lib.csr5_convert_ex.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, sz, vp, u32, C.POINTER(vp)]
     lib.csr5s_convert_ex.restype = C.c_int
     lib.csr5s_convert_ex.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, sz, vp, u32, C.POINTER(vp)]
+    lib.csr5l_workspace_bytes.restype = sz
+    lib.csr5l_workspace_bytes.argtypes = [i32, i64, i32]
+    lib.csr5l_convert_ex.restype = C.c_int
+    lib.csr5l_convert_ex.argtypes = [i32, i32, i64, vp, vp, vp, i32, vp, sz, vp, u32, C.POINTER(vp)]
+    lib.csr5l_get_arrays.restype = C.c_int
+    lib.csr5l_get_arrays.argtypes = [vp] + [C.POINTER(vp)] * 4
     lib.csr5s_spmv_ex.restype = C.c_int
     lib.csr5s_spmv_ex.argtypes = [vp, vp, vp, vp]
     lib.csr5s_spmv_profile.restype = C.c_int
@@ -165,6 +172,30 @@ def csr5s_convert_ex(m, n, nnz, row_ptr, col_idx, val, sigma=0, workspace=None, 
     return h.value if check else (rc, h.value)
 
 
+def csr5l_workspace_bytes(m, nnz, sigma=0):
+    return int(load().csr5l_workspace_bytes(int(m), int(nnz), int(sigma)))
+
+
+def csr5l_convert_ex(m, n, nnz, row_ptr, col_idx, val, sigma=0, workspace=None, stream=None,
+                     flags=CSR5_FLAG_NONE, check=True):
+    """64-bit index variant: `row_ptr` is an int64 GPU tensor, nnz may exceed 2^31."""
+    h = C.c_void_p()
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().csr5l_convert_ex(m, n, int(nnz), _ptr(row_ptr), _ptr(col_idx), _ptr(val), int(sigma),
+                                 _ptr(workspace), wsb, _stream(stream), int(flags), C.byref(h))
+    _chk(rc, "csr5l_convert_ex", check)
+    return h.value if check else (rc, h.value)
+
+
+def csr5l_get_arrays(h, check=True):
+    """Device addresses of a 64-bit-index handle's arrays."""
+    v = [C.c_void_p() for _ in range(4)]
+    rc = _chk(load().csr5l_get_arrays(h, *[C.byref(a) for a in v]), "csr5l_get_arrays", check)
+    if rc != CSR5_OK:
+        return rc
+    return dict(zip(["tile_ptr", "tile_desc", "empty_offset_ptr", "empty_offset"], [a.value for a in v]))
+
+
 def csr5s_spmv_ex(h, x, y, stream=None, check=True):
     return _chk(load().csr5s_spmv_ex(h, _ptr(x), _ptr(y), _stream(stream)), "csr5s_spmv_ex", check)
 
@@ -214,10 +245,12 @@ def csr5_get_info(h):
     return {k: a.value for k, a in zip(keys, v)}
 
 
-def csr5_get_arrays(h):
+def csr5_get_arrays(h, check=True):
     """Device addresses: dict(tile_ptr, tile_desc, empty_offset_ptr, empty_offset)."""
     v = [C.c_void_p() for _ in range(4)]
-    _chk(load().csr5_get_arrays(h, *[C.byref(a) for a in v]), "csr5_get_arrays", True)
+    rc = _chk(load().csr5_get_arrays(h, *[C.byref(a) for a in v]), "csr5_get_arrays", check)
+    if rc != CSR5_OK:
+        return rc
     return dict(zip(["tile_ptr", "tile_desc", "empty_offset_ptr", "empty_offset"], [a.value for a in v]))
 
 
@@ -232,13 +265,14 @@ def csr5_baseline_csr_vector(m, nnz, row_ptr, col_idx, val, x, y, lanes_per_row=
                 "csr5_baseline_csr_vector", check)
 
 
-def csr5_read_array(h, which):
-    """Host copy (NumPy) of one of the handle's arrays."""
+def csr5_read_array(h, which, wide=False):
+    """Host copy (NumPy) of one of the handle's arrays; wide=True for a handle
+    made by csr5l_convert_ex (8-byte tile_ptr and empty_offset_ptr entries)."""
     info = csr5_get_info(h)
     count, dtype = {
-        CSR5_ARRAY_TILE_PTR: (info["p"] + 1, np.uint32),
+        CSR5_ARRAY_TILE_PTR: (info["p"] + 1, np.uint64 if wide else np.uint32),
         CSR5_ARRAY_TILE_DESC: (info["p_complete"] * info["desc_words_per_lane"] * CSR5_OMEGA, np.uint32),
-        CSR5_ARRAY_EMPTY_OFFSET_PTR: (info["p_complete"] + 1, np.int32),
+        CSR5_ARRAY_EMPTY_OFFSET_PTR: (info["p_complete"] + 1, np.int64 if wide else np.int32),
         CSR5_ARRAY_EMPTY_OFFSET: (info["empty_offset_len"], np.int32),
     }[which]
     out = np.empty(count, dtype=dtype)

@@ -19,8 +19,6 @@ namespace {
 
 constexpr int OMEGA = CSR5_OMEGA;
 constexpr int SBITS = 6;  // ceil(log2 omega)
-constexpr uint32_t DIRTY = 0x80000000u;
-constexpr uint32_t ROWMASK = 0x7fffffffu;
 constexpr uint32_t BAD_BITS = CSR5_STATUS_BAD_ROW_PTR | CSR5_STATUS_BAD_COL_IDX;
 constexpr int NUM_XCD = 8;  // MI355X: 8 accelerator dies, each with its own L2
 
@@ -34,6 +32,21 @@ constexpr int RULE_R = 16, RULE_S = 16, RULE_T = 256, RULE_U = 16;
 // the last partial round dominate; such a matrix gets the smaller tile.
 constexpr int64_t RULE_MIN_TILES = 4 * 256 * 16;
 constexpr int RULE_SIGMA_SMALL = 8;
+
+// Index width of row_ptr, tile_ptr and empty_offset_ptr.  int32 is the layout the
+// paper describes first (tile_ptr: 31-bit row index, top bit = "tile holds an
+// empty row"); int64 is its 64-bit variant (Section 3.3: 63-bit index plus the
+// flag bit) for matrices of 2^31 nonzeros and more, which this GPU's memory holds
+// many times over.  Row and column indices stay below 2^31 in both.
+template <typename IT> struct Index;
+template <> struct Index<int32_t> {
+    using tp_t = uint32_t;
+    static constexpr tp_t DIRTY = 0x80000000u, ROWMASK = 0x7fffffffu;
+};
+template <> struct Index<int64_t> {
+    using tp_t = uint64_t;
+    static constexpr tp_t DIRTY = 0x8000000000000000ull, ROWMASK = 0x7fffffffffffffffull;
+};
 
 inline int ceil_log2_host(int64_t v) {
     int b = 0;
@@ -66,7 +79,8 @@ inline size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
 // Number of entries of a[0..len) that are <= key ("upper bound").  This is the
 // binary search of Algorithms 4 and 7: with empty rows several row_ptr entries
 // are equal, and count-1 is then the non-empty row that owns nonzero `key`.
-__device__ __forceinline__ int count_le_i32(const int32_t* __restrict__ a, int len, int64_t key) {
+template <typename IT>
+__device__ __forceinline__ int count_le(const IT* __restrict__ a, int len, int64_t key) {
     int lo = 0, hi = len;
     while (lo < hi) {
         int mid = lo + ((hi - lo) >> 1);
@@ -76,11 +90,12 @@ __device__ __forceinline__ int count_le_i32(const int32_t* __restrict__ a, int l
 }
 
 // Same over tile_ptr with the empty-row bit masked off.
-__device__ __forceinline__ int count_le_tileptr(const uint32_t* a, int len, uint32_t key) {
+template <typename IT>
+__device__ __forceinline__ int count_le_tileptr(const typename Index<IT>::tp_t* a, int len, uint32_t key) {
     int lo = 0, hi = len;
     while (lo < hi) {
         int mid = lo + ((hi - lo) >> 1);
-        uint32_t v = __hip_atomic_load(&a[mid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ROWMASK;
+        auto v = __hip_atomic_load(&a[mid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & Index<IT>::ROWMASK;
         if (v <= key) lo = mid + 1; else hi = mid;
     }
     return lo;
@@ -109,16 +124,19 @@ __device__ __forceinline__ uint32_t xcd_remap(uint32_t w, uint32_t nb) {
 // tile boundary.  The same launch clears the flag words the next kernel ORs
 // into, and the status word.
 // ----------------------------------------------------------------------------
+template <typename IT>
 __global__ void __launch_bounds__(256)
-k_tile_ptr(int m, const int32_t* __restrict__ row_ptr, int T, int p, uint32_t* __restrict__ tile_ptr,
+k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p,
+           typename Index<IT>::tp_t* __restrict__ tile_ptr,
            uint32_t* __restrict__ desc, size_t ndesc, uint32_t* __restrict__ status) {
+    using tp_t = typename Index<IT>::tp_t;
     size_t gid = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
     size_t stride = size_t(gridDim.x) * blockDim.x;
     for (size_t k = gid; k < ndesc; k += stride) desc[k] = 0u;
     if (gid == 0) *status = 0u;
     for (size_t t = gid; t <= size_t(p); t += stride) {
         int64_t bnd = int64_t(t) * T;
-        tile_ptr[t] = uint32_t(count_le_i32(row_ptr, m + 1, bnd) - 1);
+        tile_ptr[t] = tp_t(count_le(row_ptr, m + 1, bnd) - 1) & Index<IT>::ROWMASK;
     }
 }
 
@@ -132,13 +150,16 @@ k_tile_ptr(int m, const int32_t* __restrict__ row_ptr, int T, int p, uint32_t* _
 //    the scatter of Algorithm 3 step 1) directly inside the packed descriptor.
 // Also validates row_ptr.
 // ----------------------------------------------------------------------------
+template <typename IT>
 __global__ void __launch_bounds__(256)
-k_rows(int m, int nnz, const int32_t* __restrict__ row_ptr, int sigma, int T, int W, int p, int pc,
-       uint32_t* tile_ptr, uint32_t* desc, uint32_t* status) {
+k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, int p, int pc,
+       typename Index<IT>::tp_t* tile_ptr, uint32_t* desc, uint32_t* status) {
+    using tp_t = typename Index<IT>::tp_t;
+    constexpr tp_t DIRTY = Index<IT>::DIRTY;
     const int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (g >= int64_t(m)) return;
     const int r = int(g);
-    int a = row_ptr[r], b = row_ptr[r + 1];
+    IT a = row_ptr[r], b = row_ptr[r + 1];
     bool bad = (a < 0) || (b < a) || (b > nnz) || (r == 0 && a != 0) || (r == m - 1 && b != nnz);
     if (bad) {
         atomicOr(status, CSR5_STATUS_BAD_ROW_PTR);
@@ -147,14 +168,14 @@ k_rows(int m, int nnz, const int32_t* __restrict__ row_ptr, int sigma, int T, in
     if (a == b) {
         // one flag write per wavefront is enough: the lowest lane that sees an empty row
         if (lane_id() == __builtin_ctzll(__ballot(1))) atomicOr(status, CSR5_STATUS_HAS_EMPTY_ROWS);
-        int t = count_le_tileptr(tile_ptr, p + 1, uint32_t(r)) - 1;
+        int t = count_le_tileptr<IT>(tile_ptr, p + 1, uint32_t(r)) - 1;
         if (t >= 0 && t < p) {
-            uint32_t old = atomicOr(&tile_ptr[t], DIRTY);
+            tp_t old = __hip_atomic_fetch_or(&tile_ptr[t], DIRTY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (!(old & DIRTY)) atomicOr(status, CSR5_STATUS_HAS_DIRTY);
         }
     } else if (int64_t(a) < int64_t(pc) * T) {
-        int tile = a / T;
-        int w = a - tile * T;
+        int tile = int(a / T);
+        int w = int(a - IT(tile) * T);
         int i = w / sigma;
         int j = w - i * sigma;
         atomicOr(&desc[(size_t(tile) * W + (j >> 5)) * OMEGA + i], 1u << (j & 31));
@@ -168,9 +189,10 @@ k_rows(int m, int nnz, const int32_t* __restrict__ row_ptr, int sigma, int T, in
 // the run length are wavefront operations here), packing (Section 3.5), and the
 // tile's segment count for the empty_offset layout.
 // ----------------------------------------------------------------------------
+template <typename IT>
 __global__ void __launch_bounds__(256)
-k_tile_desc(int sigma, int W, int ybits, int pc, const uint32_t* __restrict__ tile_ptr,
-            uint32_t* __restrict__ desc, int32_t* __restrict__ eop) {
+k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
+            uint32_t* __restrict__ desc, IT* __restrict__ eop) {
     int tile = blockIdx.x * (blockDim.x / OMEGA) + (threadIdx.x / OMEGA);
     if (tile >= pc) return;
     int lane = lane_id();
@@ -198,7 +220,7 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const uint32_t* __restrict__ ti
     desc[base] = uint32_t(lo);
     if (W > 1) desc[base + OMEGA] = uint32_t(lo >> 32);
     if (W > 2) desc[base + 2 * OMEGA] = uint32_t(hi);
-    if (lane == 0) eop[tile] = (tile_ptr[tile] & DIRTY) ? total : 0;
+    if (lane == 0) eop[tile] = (tile_ptr[tile] & Index<IT>::DIRTY) ? total : 0;
 }
 
 // ----------------------------------------------------------------------------
@@ -207,47 +229,48 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const uint32_t* __restrict__ ti
 // p_c + 1 entries.  Skipped when no tile is marked.
 // ----------------------------------------------------------------------------
 constexpr int SCAN_THREADS = 1024, SCAN_ITEMS = 8;
+template <typename IT>
 __global__ void __launch_bounds__(SCAN_THREADS)
-k_scan_eop(int pc, int32_t* __restrict__ eop, const uint32_t* __restrict__ status) {
+k_scan_eop(int pc, IT* __restrict__ eop, const uint32_t* __restrict__ status) {
     if (!(*status & CSR5_STATUS_HAS_DIRTY)) {
         if (threadIdx.x == 0) eop[pc] = 0;
         return;
     }
-    __shared__ int wave_sum[SCAN_THREADS / OMEGA];
-    __shared__ int chunk_total;
+    __shared__ IT wave_sum[SCAN_THREADS / OMEGA];
+    __shared__ IT chunk_total;
     int lane = lane_id(), wave = threadIdx.x / OMEGA;
-    int carry = 0;
-    for (int base = 0; base < pc; base += SCAN_THREADS * SCAN_ITEMS) {
-        int idx0 = base + threadIdx.x * SCAN_ITEMS;
-        int local[SCAN_ITEMS];
-        int s = 0;
+    IT carry = 0;
+    for (int64_t base = 0; base < pc; base += SCAN_THREADS * SCAN_ITEMS) {
+        int64_t idx0 = base + threadIdx.x * SCAN_ITEMS;
+        IT local[SCAN_ITEMS];
+        IT s = 0;
 #pragma unroll
         for (int q = 0; q < SCAN_ITEMS; q++) {
-            int v = (idx0 + q < pc) ? eop[idx0 + q] : 0;
+            IT v = (idx0 + q < pc) ? eop[idx0 + q] : IT(0);
             local[q] = s;
             s += v;
         }
-        int incl = s;
+        IT incl = s;
 #pragma unroll
         for (int d = 1; d < OMEGA; d <<= 1) {
-            int up = __shfl_up(incl, d, OMEGA);
+            IT up = __shfl_up(incl, d, OMEGA);
             if (lane >= d) incl += up;
         }
         if (lane == OMEGA - 1) wave_sum[wave] = incl;
         __syncthreads();
         if (wave == 0) {
-            int v = (lane < SCAN_THREADS / OMEGA) ? wave_sum[lane] : 0;
-            int ws = v;
+            IT v = (lane < SCAN_THREADS / OMEGA) ? wave_sum[lane] : IT(0);
+            IT ws = v;
 #pragma unroll
             for (int d = 1; d < SCAN_THREADS / OMEGA; d <<= 1) {
-                int up = __shfl_up(ws, d, OMEGA);
+                IT up = __shfl_up(ws, d, OMEGA);
                 if (lane >= d) ws += up;
             }
             if (lane < SCAN_THREADS / OMEGA) wave_sum[lane] = ws - v;  // exclusive
             if (lane == SCAN_THREADS / OMEGA - 1) chunk_total = ws;
         }
         __syncthreads();
-        int excl = carry + wave_sum[wave] + incl - s;
+        IT excl = carry + wave_sum[wave] + incl - s;
 #pragma unroll
         for (int q = 0; q < SCAN_ITEMS; q++)
             if (idx0 + q < pc) eop[idx0 + q] = excl + local[q];
@@ -266,11 +289,14 @@ k_scan_eop(int pc, int32_t* __restrict__ eop, const uint32_t* __restrict__ statu
 // tile, which is then the tile's first row): its entry is 0 and is written by
 // the extra p_c threads at the end of the grid.
 // ----------------------------------------------------------------------------
+template <typename IT>
 __global__ void __launch_bounds__(256)
-k_empty_offset(int m, const int32_t* __restrict__ row_ptr, int sigma, int T, int W, int pc,
-               const uint32_t* __restrict__ tile_ptr, const uint32_t* __restrict__ desc,
-               const int32_t* __restrict__ eop, int32_t* __restrict__ eo,
+k_empty_offset(int m, const IT* __restrict__ row_ptr, int sigma, int T, int W, int pc,
+               const typename Index<IT>::tp_t* __restrict__ tile_ptr, const uint32_t* __restrict__ desc,
+               const IT* __restrict__ eop, int32_t* __restrict__ eo,
                const uint32_t* __restrict__ status) {
+    using tp_t = typename Index<IT>::tp_t;
+    constexpr tp_t DIRTY = Index<IT>::DIRTY, ROWMASK = Index<IT>::ROWMASK;
     uint32_t st = *status;
     if (!(st & CSR5_STATUS_HAS_DIRTY) || (st & BAD_BITS)) return;
     int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -280,12 +306,12 @@ k_empty_offset(int m, const int32_t* __restrict__ row_ptr, int sigma, int T, int
         return;
     }
     int r = int(g);
-    int a = row_ptr[r], b = row_ptr[r + 1];
+    IT a = row_ptr[r], b = row_ptr[r + 1];
     if (a == b || int64_t(a) >= int64_t(pc) * T) return;
-    int tile = a / T;
-    uint32_t tp = tile_ptr[tile];
+    int tile = int(a / T);
+    tp_t tp = tile_ptr[tile];
     if (!(tp & DIRTY)) return;
-    int w = a - tile * T;
+    int w = int(a - IT(tile) * T);
     int i = w / sigma;
     int j = w - i * sigma;
     size_t base = size_t(tile) * W * OMEGA + i;
@@ -298,7 +324,7 @@ k_empty_offset(int m, const int32_t* __restrict__ row_ptr, int sigma, int T, int
     // y_offset occupies every bit above seg_offset (unused high bits are zero)
     uint64_t below = lo & ((uint64_t(1) << j) - 1);
     int seg = int(yo) + __popcll(below);
-    eo[eop[tile] + seg] = r - int(tp & ROWMASK);
+    eo[eop[tile] + seg] = int32_t(int64_t(r) - int64_t(tp & ROWMASK));
 }
 
 // ----------------------------------------------------------------------------
@@ -328,7 +354,7 @@ __device__ __forceinline__ void wave_sync_lds() {
 
 template <int SIGMA, bool BACK, typename VT>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
-k_transpose(int pc, int n, int nnz, int32_t* __restrict__ col_idx, VT* __restrict__ val,
+k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __restrict__ val,
             uint32_t* __restrict__ status) {
     constexpr int T = OMEGA * SIGMA;
     constexpr int PITCH = TransposeShape<SIGMA>::PITCH;
@@ -465,9 +491,9 @@ constexpr int TAIL_MAX_CHUNKS = (CSR5_SIGMA_MAX * OMEGA) / OMEGA + 1;   // 64-en
 // slot of the chunk it starts in (at most one row starts in a chunk and leaves
 // it), and stored at the end.  The part of a row that began in the complete
 // tiles goes to carry[pc] like a tile's segment 0.
-template <typename VT>
-__device__ void spmv_tail(int m, int nnz, int first, uint32_t tile_ptr_last,
-                          const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+template <typename VT, typename IT>
+__device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
+                          const IT* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                           const VT* __restrict__ val, const VT* __restrict__ x,
                           VT* __restrict__ y, VT* __restrict__ carry_slot) {
     __shared__ VT acc[TAIL_MAX_CHUNKS];
@@ -478,18 +504,17 @@ __device__ void spmv_tail(int m, int nnz, int first, uint32_t tile_ptr_last,
     for (int q = threadIdx.x; q < TAIL_MAX_CHUNKS; q += blockDim.x) { acc[q] = VT(0); acc_row[q] = -1; }
     if (threadIdx.x == 0) acc_first = VT(0);
     __syncthreads();
-    int row_lo = int(tile_ptr_last & ROWMASK);
-    if (row_lo > m) row_lo = m;
-    const int span = nnz - first;
+    int row_lo = row_first > uint32_t(m) ? m : int(row_first);
+    const int span = int(nnz - first);                   // < one tile
     const int nchunks = (span + OMEGA - 1) / OMEGA;
     for (int q = wave; q < nchunks && q < TAIL_MAX_CHUNKS; q += nwaves) {
-        const int chunk_lo = first + q * OMEGA;
-        const int e = chunk_lo + lane;
+        const IT chunk_lo = first + q * OMEGA;
+        const IT e = chunk_lo + lane;
         const bool live = e < nnz;
         int row = -2 - lane;                         // distinct keys for dead lanes
         VT prod = VT(0);
         if (live) {
-            row = row_lo + count_le_i32(row_ptr + row_lo, m + 1 - row_lo, e) - 1;
+            row = row_lo + count_le(row_ptr + row_lo, m + 1 - row_lo, e) - 1;
             prod = val[e] * x[col_idx[e]];
         }
 #pragma unroll
@@ -501,13 +526,13 @@ __device__ void spmv_tail(int m, int nnz, int first, uint32_t tile_ptr_last,
         int rnext = __shfl_down(row, 1, OMEGA);
         bool run_end = live && ((lane == OMEGA - 1) || (rnext != row));
         if (run_end && row >= 0 && row < m) {
-            int rs = row_ptr[row], re = row_ptr[row + 1];
+            IT rs = row_ptr[row], re = row_ptr[row + 1];
             if (rs >= chunk_lo && re <= chunk_lo + OMEGA) {
                 y[row] = prod;                       // the whole row lies in this chunk
             } else if (rs < first) {
                 atomicAdd(&acc_first, prod);         // continues a row of the complete tiles
             } else {
-                int q1 = (rs - first) / OMEGA;       // chunk the row starts in
+                int q1 = int((rs - first) / OMEGA);  // chunk the row starts in
                 if (q1 >= 0 && q1 < TAIL_MAX_CHUNKS) {
                     atomicAdd(&acc[q1], prod);
                     acc_row[q1] = row;
@@ -521,11 +546,11 @@ __device__ void spmv_tail(int m, int nnz, int first, uint32_t tile_ptr_last,
     if (threadIdx.x == 0) *carry_slot = acc_first;
 }
 
-template <int SIGMA, typename VT>
+template <int SIGMA, typename VT, typename IT>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
-k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
-       const int32_t* __restrict__ row_ptr, const uint32_t* __restrict__ tile_ptr,
-       const uint32_t* __restrict__ tile_desc, const int32_t* __restrict__ eop,
+k_spmv(int m, IT nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
+       const IT* __restrict__ row_ptr, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
+       const uint32_t* __restrict__ tile_desc, const IT* __restrict__ eop,
        const int32_t* __restrict__ eo, const int32_t* __restrict__ col_idx,
        const VT* __restrict__ val, const VT* __restrict__ x, VT* __restrict__ y,
        VT* __restrict__ carry, const uint32_t* __restrict__ status) {
@@ -536,13 +561,16 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
     constexpr int PITCH = TransposeShape<SIGMA>::PITCH;
     using flag_t = typename FlagWord<SIGMA>::type;
+    using tp_t = typename Index<IT>::tp_t;
     __shared__ double lds[WAVES][OMEGA * PITCH];
 
     const uint32_t st = *status;      // consulted below, after the streaming loads are in flight
 
     if (blockIdx.x < has_tail) {      // workgroup 0: incomplete last tile
         if (st & BAD_BITS) return;
-        spmv_tail(m, nnz, pc * T, tile_ptr[pc], row_ptr, col_idx, val, x, y, carry + pc);
+        const tp_t first_row = tile_ptr[pc] & Index<IT>::ROWMASK;
+        spmv_tail<VT, IT>(m, nnz, IT(pc) * T, first_row > tp_t(m) ? uint32_t(m) : uint32_t(first_row),
+                          row_ptr, col_idx, val, x, y, carry + pc);
         return;
     }
     const int lane = lane_id();
@@ -569,9 +597,10 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     for (int j = 0; j < SIGMA; j++) v[j] = __builtin_nontemporal_load(&val[tile_base + j * OMEGA + lane]);
 
     // ---- descriptor
-    const uint32_t tp = tile_ptr[tile];
-    const bool dirty = (tp & DIRTY) != 0;
-    const uint32_t row0 = tp & ROWMASK;
+    const tp_t tp = tile_ptr[tile];
+    const bool dirty = (tp & Index<IT>::DIRTY) != 0;
+    const tp_t row0_wide = tp & Index<IT>::ROWMASK;
+    const uint32_t row0 = uint32_t(row0_wide);
     const uint32_t* dp = tile_desc + size_t(tile) * W * OMEGA + lane;
     uint64_t lo = __builtin_nontemporal_load(dp);
     if (W > 1) lo |= uint64_t(__builtin_nontemporal_load(dp + OMEGA)) << 32;
@@ -586,13 +615,13 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     const int32_t* eo_t = nullptr;
     uint32_t nseg_t = 0;
     if (dirty) {
-        int32_t e0 = eop[tile], e1 = eop[tile + 1];
+        IT e0 = eop[tile], e1 = eop[tile + 1];
         eo_t = eo + e0;
         nseg_t = uint32_t(e1 - e0);
     }
-    if ((st & BAD_BITS) || row0 >= uint32_t(m)) return;   // rejected input: gather and store nothing
+    if ((st & BAD_BITS) || row0_wide >= tp_t(m)) return;  // rejected input: gather and store nothing
     // does segment 0 continue a row that an earlier tile opened?
-    const bool cont0 = row_ptr[row0] != tile * T;
+    const bool cont0 = row_ptr[row0] != IT(tile) * T;
 
     // ---- gather x.  Lane i owns the CSR entries i*sigma .. i*sigma+sigma-1 of the
     // tile, so at a fixed step the 64 lanes would gather from 64 unrelated
@@ -706,11 +735,16 @@ k_spmv(int m, int nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
 // Rows without nonzeros are stored by no tile; they get their 0 here when the
 // matrix has any (status bit set during conversion).
 // ----------------------------------------------------------------------------
-template <typename VT>
+template <typename VT, typename IT>
 __global__ void __launch_bounds__(256)
-k_spmv_fixup(int m, int ntiles, const int32_t* __restrict__ row_ptr,
-             const uint32_t* __restrict__ tile_ptr, const VT* __restrict__ carry,
+k_spmv_fixup(int m, int ntiles, const IT* __restrict__ row_ptr,
+             const typename Index<IT>::tp_t* __restrict__ tile_ptr, const VT* __restrict__ carry,
              VT* __restrict__ y, const uint32_t* __restrict__ status) {
+    // rows are below 2^31 whatever the index width; 0xfff... marks "no tile"
+    auto first_row = [&](int t) -> uint32_t {
+        auto v = tile_ptr[t] & Index<IT>::ROWMASK;
+        return v > 0x7fffffffu ? 0x7fffffffu : uint32_t(v);
+    };
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = lane_id();
     const int t0 = gid - lane;                            // first tile of this wavefront
@@ -718,10 +752,10 @@ k_spmv_fixup(int m, int ntiles, const int32_t* __restrict__ row_ptr,
     // Everything that does not depend on other loads is requested at once: the
     // kernel is a chain of memory round trips and nothing else.
     const uint32_t st = *status;
-    const uint32_t R = live ? (tile_ptr[gid] & ROWMASK) : (0xfffffff0u - uint32_t(lane));
+    const uint32_t R = live ? first_row(gid) : (0xfffffff0u - uint32_t(lane));
     VT cs = live ? carry[gid] : VT(0);
-    const uint32_t r_after = (gid + 1 < ntiles) ? (tile_ptr[gid + 1] & ROWMASK) : 0xffffffffu;
-    const uint32_t r_before = (t0 > 0 && t0 < ntiles) ? (tile_ptr[t0 - 1] & ROWMASK) : 0xffffffffu;
+    const uint32_t r_after = (gid + 1 < ntiles) ? first_row(gid + 1) : 0xffffffffu;
+    const uint32_t r_before = (t0 > 0 && t0 < ntiles) ? first_row(t0 - 1) : 0xffffffffu;
     if (st & BAD_BITS) return;
     if (st & CSR5_STATUS_HAS_EMPTY_ROWS) {
         const int64_t stride = int64_t(gridDim.x) * blockDim.x;
@@ -746,9 +780,10 @@ k_spmv_fixup(int m, int ntiles, const int32_t* __restrict__ row_ptr,
     }
 }
 
-template <int SIGMA, typename VT>
-hipError_t launch_spmv(const Geom& g, int m, int nnz, const int32_t* row_ptr, const uint32_t* tile_ptr,
-                       const uint32_t* tile_desc, const int32_t* eop, const int32_t* eo,
+template <int SIGMA, typename VT, typename IT>
+hipError_t launch_spmv(const Geom& g, int m, IT nnz, const IT* row_ptr,
+                       const typename Index<IT>::tp_t* tile_ptr,
+                       const uint32_t* tile_desc, const IT* eop, const int32_t* eo,
                        const int32_t* col_idx, const VT* val, const VT* x, VT* y,
                        VT* carry, const uint32_t* status, hipStream_t s) {
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
@@ -756,13 +791,13 @@ hipError_t launch_spmv(const Geom& g, int m, int nnz, const int32_t* row_ptr, co
     uint32_t has_tail = (int64_t(g.pc) * g.T < nnz) ? 1u : 0u;
     uint32_t nb = nb_tiles + has_tail;
     if (nb == 0) return hipSuccess;
-    hipLaunchKernelGGL((k_spmv<SIGMA, VT>), dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, nb_tiles, has_tail,
+    hipLaunchKernelGGL((k_spmv<SIGMA, VT, IT>), dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, nb_tiles, has_tail,
                        row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status);
     return hipGetLastError();
 }
 
 template <int SIGMA, bool BACK, typename VT>
-hipError_t launch_transpose(const Geom& g, int n, int nnz, int32_t* col_idx, VT* val,
+hipError_t launch_transpose(const Geom& g, int n, int64_t nnz, int32_t* col_idx, VT* val,
                             uint32_t* status, hipStream_t s) {
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
     uint32_t nb = uint32_t((g.pc + WAVES - 1) / WAVES);
@@ -819,15 +854,17 @@ k_csr_vector(int m, const int32_t* __restrict__ row_ptr, const int32_t* __restri
 // handle
 // ----------------------------------------------------------------------------
 struct csr5_handle_s {
-    int32_t m, n, nnz;
+    int32_t m, n;
+    int64_t nnz;
     Geom g;
-    const int32_t* row_ptr;
+    bool wide;             // 64-bit row_ptr, tile_ptr and empty_offset_ptr (csr5l_convert_ex)
+    const void* row_ptr;   // int32_t* or int64_t*
     int32_t* col_idx;
     void* val;             // double* or float*, see dtype
     int dtype;             // CSR5_DTYPE_F64 / CSR5_DTYPE_F32
-    uint32_t* tile_ptr;
+    void* tile_ptr;        // uint32_t* or uint64_t*
     uint32_t* tile_desc;
-    int32_t* eop;
+    void* eop;             // int32_t* or int64_t*
     int32_t* eo;
     uint32_t* status;
     void* carry;           // one 8-byte slot per tile (incomplete one included): cross-tile sums of an SpMV
@@ -843,21 +880,30 @@ struct Layout {
     size_t ndesc, eo_cap;
 };
 
-Layout make_layout(int32_t m, const Geom& g) {
+Layout make_layout(int32_t m, const Geom& g, bool wide) {
     Layout L;
+    const size_t isz = wide ? 8 : 4;   // bytes of one tile_ptr / empty_offset_ptr entry
     L.ndesc = size_t(g.pc) * g.W * OMEGA;
     size_t cap_a = size_t(m) + size_t(g.pc);
     size_t cap_b = size_t(g.pc) * g.T;
     L.eo_cap = cap_a < cap_b ? cap_a : cap_b;
     size_t o = 0;
-    L.off_tile_ptr = o; o += align256((size_t(g.p) + 1) * 4);
+    L.off_tile_ptr = o; o += align256((size_t(g.p) + 1) * isz);
     L.off_desc = o;     o += align256(L.ndesc * 4);
-    L.off_eop = o;      o += align256((size_t(g.pc) + 1) * 4);
+    L.off_eop = o;      o += align256((size_t(g.pc) + 1) * isz);
     L.off_eo = o;       o += align256(L.eo_cap * 4);
     L.off_carry = o;    o += align256((size_t(g.p) + 1) * 8);
     L.off_status = o;   o += 256;
     L.total = o;
     return L;
+}
+
+// Largest matrix the launches can address: one wavefront per tile and at most
+// 2^32 - 1 threads in a grid; the row-parallel kernels add p_c threads to m.
+bool geometry_fits(int64_t m, int64_t nnz, int sigma) {
+    const int64_t T = int64_t(OMEGA) * sigma;
+    const int64_t p = (nnz + T - 1) / T;
+    return p < (int64_t(1) << 26) - 4 && m + p < (int64_t(1) << 32) - 512;
 }
 
 }  // namespace
@@ -870,7 +916,7 @@ const char* csr5_strerror(int code) {
         case CSR5_EINVAL: return "invalid argument";
         case CSR5_ENOMEM: return "out of memory or workspace too small";
         case CSR5_EHIP: return "HIP runtime error";
-        case CSR5_ERANGE: return "sigma out of range";
+        case CSR5_ERANGE: return "sigma out of range, or matrix too large for the index width";
         default: return "unknown error";
     }
 }
@@ -889,15 +935,25 @@ size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma) {
     if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
     if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX) return 0;
     Geom g = make_geom(nnz, sigma);
-    return make_layout(m, g).total;
+    return make_layout(m, g, false).total;
+}
+
+size_t csr5l_workspace_bytes(int32_t m, int64_t nnz, int32_t sigma) {
+    if (m < 0 || nnz < 0) return 0;
+    if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
+    if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX || !geometry_fits(m, nnz, sigma)) return 0;
+    Geom g = make_geom(nnz, sigma);
+    return make_layout(m, g, true).total;
 }
 
 }  // extern "C"
 
-template <typename VT>
-static int convert_impl(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
+template <typename VT, typename IT>
+static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t* col_idx,
                         VT* val, int32_t sigma, void* workspace, size_t workspace_bytes,
                         void* hip_stream, uint32_t flags, csr5_handle_t* out) {
+    using tp_t = typename Index<IT>::tp_t;
+    constexpr bool wide = sizeof(IT) == 8;
     if (!out) return CSR5_EINVAL;
     *out = nullptr;
     if (m < 0 || n < 0 || nnz < 0) return CSR5_EINVAL;
@@ -905,21 +961,22 @@ static int convert_impl(int32_t m, int32_t n, int32_t nnz, const int32_t* row_pt
     if (nnz > 0 && (!col_idx || !val || m == 0 || n == 0)) return CSR5_EINVAL;
     // the kernels read col_idx with 16-byte accesses and val element-wise
     if ((reinterpret_cast<uintptr_t>(col_idx) & 15) || (reinterpret_cast<uintptr_t>(val) & (sizeof(VT) - 1)) ||
-        (reinterpret_cast<uintptr_t>(row_ptr) & 3)) return CSR5_EINVAL;
+        (reinterpret_cast<uintptr_t>(row_ptr) & (sizeof(IT) - 1))) return CSR5_EINVAL;
     if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
     if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX) return CSR5_ERANGE;
+    if (!geometry_fits(m, nnz, sigma)) return CSR5_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
     if (!(flags & CSR5_FLAG_NO_HOST_CHECK)) {
-        int32_t ends[2] = {0, nnz};
-        if (hipMemcpyAsync(&ends[0], row_ptr, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return CSR5_EHIP;
-        if (hipMemcpyAsync(&ends[1], row_ptr + m, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return CSR5_EHIP;
+        IT ends[2] = {0, nnz};
+        if (hipMemcpyAsync(&ends[0], row_ptr, sizeof(IT), hipMemcpyDeviceToHost, s) != hipSuccess) return CSR5_EHIP;
+        if (hipMemcpyAsync(&ends[1], row_ptr + m, sizeof(IT), hipMemcpyDeviceToHost, s) != hipSuccess) return CSR5_EHIP;
         if (hipStreamSynchronize(s) != hipSuccess) return CSR5_EHIP;
         if (ends[0] != 0 || ends[1] != nnz) return CSR5_EINVAL;
     }
 
     Geom g = make_geom(nnz, sigma);
-    Layout L = make_layout(m, g);
+    Layout L = make_layout(m, g, wide);
     csr5_handle_s* h = new (std::nothrow) csr5_handle_s();
     if (!h) return CSR5_ENOMEM;
     char* basep = nullptr;
@@ -940,45 +997,47 @@ static int convert_impl(int32_t m, int32_t n, int32_t nnz, const int32_t* row_pt
         basep = static_cast<char*>(ptr);
         h->owned = ptr;
     }
-    h->m = m; h->n = n; h->nnz = nnz; h->g = g;
+    h->m = m; h->n = n; h->nnz = nnz; h->g = g; h->wide = wide;
     h->row_ptr = row_ptr; h->col_idx = col_idx; h->val = val;
     h->dtype = std::is_same<VT, float>::value ? CSR5_DTYPE_F32 : CSR5_DTYPE_F64;
-    h->tile_ptr = reinterpret_cast<uint32_t*>(basep + L.off_tile_ptr);
+    h->tile_ptr = basep + L.off_tile_ptr;
     h->tile_desc = reinterpret_cast<uint32_t*>(basep + L.off_desc);
-    h->eop = reinterpret_cast<int32_t*>(basep + L.off_eop);
+    h->eop = basep + L.off_eop;
     h->eo = reinterpret_cast<int32_t*>(basep + L.off_eo);
     h->carry = basep + L.off_carry;
     h->status = reinterpret_cast<uint32_t*>(basep + L.off_status);
     h->conv_stream = s;
     h->in_csr5_order = true;
+    tp_t* const tile_ptr = static_cast<tp_t*>(h->tile_ptr);
+    IT* const eop = static_cast<IT*>(h->eop);
 
     hipError_t e = hipSuccess;
     {   // step 2a (+ clearing)
         size_t work = L.ndesc > size_t(g.p) + 1 ? L.ndesc : size_t(g.p) + 1;
         size_t nb = (work + 255) / 256;
         if (nb > 8192) nb = 8192;
-        hipLaunchKernelGGL(k_tile_ptr, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p,
-                           h->tile_ptr, h->tile_desc, L.ndesc, h->status);
+        hipLaunchKernelGGL(k_tile_ptr<IT>, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p,
+                           tile_ptr, h->tile_desc, L.ndesc, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && m > 0) {   // steps 2b + 3a
-        hipLaunchKernelGGL(k_rows, dim3(uint32_t((size_t(m) + 255) / 256)), dim3(256), 0, s, m, nnz,
-                           row_ptr, g.sigma, g.T, g.W, g.p, g.pc, h->tile_ptr, h->tile_desc, h->status);
+        hipLaunchKernelGGL(k_rows<IT>, dim3(uint32_t((size_t(m) + 255) / 256)), dim3(256), 0, s, m, nnz,
+                           row_ptr, g.sigma, g.T, g.W, g.p, g.pc, tile_ptr, h->tile_desc, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && g.pc > 0) {   // step 3b
-        hipLaunchKernelGGL(k_tile_desc, dim3(uint32_t((g.pc + 3) / 4)), dim3(256), 0, s, g.sigma, g.W,
-                           g.ybits, g.pc, h->tile_ptr, h->tile_desc, h->eop);
+        hipLaunchKernelGGL(k_tile_desc<IT>, dim3(uint32_t((g.pc + 3) / 4)), dim3(256), 0, s, g.sigma, g.W,
+                           g.ybits, g.pc, tile_ptr, h->tile_desc, eop);
         e = hipGetLastError();
     }
     if (e == hipSuccess) {
-        hipLaunchKernelGGL(k_scan_eop, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, h->eop, h->status);
+        hipLaunchKernelGGL(k_scan_eop<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, eop, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && g.pc > 0 && m > 0) {
         size_t threads = size_t(m) + size_t(g.pc);
-        hipLaunchKernelGGL(k_empty_offset, dim3(uint32_t((threads + 255) / 256)), dim3(256), 0, s, m,
-                           row_ptr, g.sigma, g.T, g.W, g.pc, h->tile_ptr, h->tile_desc, h->eop, h->eo,
+        hipLaunchKernelGGL(k_empty_offset<IT>, dim3(uint32_t((threads + 255) / 256)), dim3(256), 0, s, m,
+                           row_ptr, g.sigma, g.T, g.W, g.pc, tile_ptr, h->tile_desc, eop, h->eo,
                            h->status);
         e = hipGetLastError();
     }
@@ -1021,15 +1080,22 @@ extern "C" {
 int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
                     double* val, int32_t sigma, void* workspace, size_t workspace_bytes,
                     void* hip_stream, uint32_t flags, csr5_handle_t* out) {
-    return convert_impl<double>(m, n, nnz, row_ptr, col_idx, val, sigma, workspace, workspace_bytes,
-                                hip_stream, flags, out);
+    return convert_impl<double, int32_t>(m, n, nnz, row_ptr, col_idx, val, sigma, workspace, workspace_bytes,
+                                         hip_stream, flags, out);
+}
+
+int csr5l_convert_ex(int32_t m, int32_t n, int64_t nnz, const int64_t* row_ptr, int32_t* col_idx,
+                     double* val, int32_t sigma, void* workspace, size_t workspace_bytes,
+                     void* hip_stream, uint32_t flags, csr5_handle_t* out) {
+    return convert_impl<double, int64_t>(m, n, nnz, row_ptr, col_idx, val, sigma, workspace, workspace_bytes,
+                                         hip_stream, flags, out);
 }
 
 int csr5s_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
                      float* val, int32_t sigma, void* workspace, size_t workspace_bytes,
                      void* hip_stream, uint32_t flags, csr5_handle_t* out) {
-    return convert_impl<float>(m, n, nnz, row_ptr, col_idx, val, sigma, workspace, workspace_bytes,
-                               hip_stream, flags, out);
+    return convert_impl<float, int32_t>(m, n, nnz, row_ptr, col_idx, val, sigma, workspace, workspace_bytes,
+                                        hip_stream, flags, out);
 }
 
 int csr5_convert(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int32_t* col_idx,
@@ -1041,16 +1107,20 @@ int csr5_convert(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int3
 
 // One SpMV: the tile kernel, then the carry fix-up.  `ev`, when given, points at
 // three events recorded before, between and after the two launches.
-template <typename VT>
-static int spmv_launch(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, hipEvent_t* ev) {
+template <typename VT, typename IT>
+static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, hipEvent_t* ev) {
+    using tp_t = typename Index<IT>::tp_t;
+    const IT* row_ptr = static_cast<const IT*>(h->row_ptr);
+    const tp_t* tile_ptr = static_cast<const tp_t*>(h->tile_ptr);
+    const IT* eop = static_cast<const IT*>(h->eop);
     if (ev && hipEventRecord(ev[0], s) != hipSuccess) return CSR5_EHIP;
     hipError_t e = hipSuccess;
     VT* carry = static_cast<VT*>(h->carry);
     if (h->nnz > 0) {
         switch (h->g.sigma) {
-#define X(S) case S: e = launch_spmv<S, VT>(h->g, h->m, h->nnz, h->row_ptr, h->tile_ptr, h->tile_desc, h->eop, \
-                                            h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y, carry,  \
-                                            h->status, s); break;
+#define X(S) case S: e = launch_spmv<S, VT, IT>(h->g, h->m, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, eop, \
+                                                h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y,    \
+                                                carry, h->status, s); break;
             CSR5_FOR_SIGMA(X)
 #undef X
             default: e = hipErrorInvalidValue;
@@ -1066,12 +1136,22 @@ static int spmv_launch(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, hipEv
         if (nb_rows > 512) nb_rows = 512;
         if (nb < nb_rows) nb = nb_rows;
         if (nb == 0) nb = 1;
-        hipLaunchKernelGGL(k_spmv_fixup<VT>, dim3(uint32_t(nb)), dim3(256), 0, s, h->m, ntiles, h->row_ptr,
-                           h->tile_ptr, carry, y, h->status);
+        hipLaunchKernelGGL((k_spmv_fixup<VT, IT>), dim3(uint32_t(nb)), dim3(256), 0, s, h->m, ntiles, row_ptr,
+                           tile_ptr, carry, y, h->status);
         if (hipGetLastError() != hipSuccess) return CSR5_EHIP;
     }
     if (ev && hipEventRecord(ev[2], s) != hipSuccess) return CSR5_EHIP;
     return CSR5_OK;
+}
+
+// The 64-bit index variant exists for double only.
+template <typename VT>
+static int spmv_launch(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, hipEvent_t* ev) {
+    if constexpr (std::is_same<VT, double>::value) {
+        if (h->wide) return spmv_launch_it<double, int64_t>(h, x, y, s, ev);
+    }
+    if (h->wide) return CSR5_EINVAL;
+    return spmv_launch_it<VT, int32_t>(h, x, y, s, ev);
 }
 
 template <typename VT>
@@ -1180,20 +1260,33 @@ int csr5_get_info(csr5_handle_t h, int32_t* omega, int32_t* sigma, int32_t* p, i
     if (p_complete) *p_complete = h->g.pc;
     if (desc_words_per_lane) *desc_words_per_lane = h->g.W;
     if (empty_offset_len) {
-        int32_t v = 0;
-        if (hipMemcpyAsync(&v, h->eop + h->g.pc, 4, hipMemcpyDeviceToHost, h->conv_stream) != hipSuccess) return CSR5_EHIP;
+        int64_t v = 0;
+        const size_t isz = h->wide ? 8 : 4;   // little-endian host: a 4-byte count lands in the low half
+        const char* src = static_cast<const char*>(h->eop) + size_t(h->g.pc) * isz;
+        if (hipMemcpyAsync(&v, src, isz, hipMemcpyDeviceToHost, h->conv_stream) != hipSuccess) return CSR5_EHIP;
         if (hipStreamSynchronize(h->conv_stream) != hipSuccess) return CSR5_EHIP;
-        *empty_offset_len = v;
+        if (v < 0 || v > INT32_MAX) return CSR5_ERANGE;
+        *empty_offset_len = int32_t(v);
     }
     return CSR5_OK;
 }
 
 int csr5_get_arrays(csr5_handle_t h, const uint32_t** tile_ptr, const uint32_t** tile_desc,
                     const int32_t** empty_offset_ptr, const int32_t** empty_offset) {
-    if (!h) return CSR5_EINVAL;
-    if (tile_ptr) *tile_ptr = h->tile_ptr;
+    if (!h || h->wide) return CSR5_EINVAL;
+    if (tile_ptr) *tile_ptr = static_cast<const uint32_t*>(h->tile_ptr);
     if (tile_desc) *tile_desc = h->tile_desc;
-    if (empty_offset_ptr) *empty_offset_ptr = h->eop;
+    if (empty_offset_ptr) *empty_offset_ptr = static_cast<const int32_t*>(h->eop);
+    if (empty_offset) *empty_offset = h->eo;
+    return CSR5_OK;
+}
+
+int csr5l_get_arrays(csr5_handle_t h, const uint64_t** tile_ptr, const uint32_t** tile_desc,
+                     const int64_t** empty_offset_ptr, const int32_t** empty_offset) {
+    if (!h || !h->wide) return CSR5_EINVAL;
+    if (tile_ptr) *tile_ptr = static_cast<const uint64_t*>(h->tile_ptr);
+    if (tile_desc) *tile_desc = h->tile_desc;
+    if (empty_offset_ptr) *empty_offset_ptr = static_cast<const int64_t*>(h->eop);
     if (empty_offset) *empty_offset = h->eo;
     return CSR5_OK;
 }
@@ -1236,9 +1329,9 @@ int csr5_read_array(csr5_handle_t h, int which, void* dst_host, size_t bytes) {
     const void* src = nullptr;
     size_t have = 0;
     switch (which) {
-        case CSR5_ARRAY_TILE_PTR: src = h->tile_ptr; have = (size_t(h->g.p) + 1) * 4; break;
+        case CSR5_ARRAY_TILE_PTR: src = h->tile_ptr; have = (size_t(h->g.p) + 1) * (h->wide ? 8 : 4); break;
         case CSR5_ARRAY_TILE_DESC: src = h->tile_desc; have = size_t(h->g.pc) * h->g.W * OMEGA * 4; break;
-        case CSR5_ARRAY_EMPTY_OFFSET_PTR: src = h->eop; have = (size_t(h->g.pc) + 1) * 4; break;
+        case CSR5_ARRAY_EMPTY_OFFSET_PTR: src = h->eop; have = (size_t(h->g.pc) + 1) * (h->wide ? 8 : 4); break;
         case CSR5_ARRAY_EMPTY_OFFSET: {
             int32_t len = 0;
             int rc = csr5_get_info(h, nullptr, nullptr, nullptr, nullptr, nullptr, &len);

@@ -11,10 +11,11 @@ TOL_ABS = 1e-300
 
 
 class DeviceCsr:
-    def __init__(self, a):
+    def __init__(self, a, wide=False):
         dev = torch.device("cuda:0")
         self.a = a
-        self.row_ptr = torch.from_numpy(a.row_ptr).to(dev)
+        self.wide = wide            # 64-bit index variant: int64 row_ptr, csr5l_ entry points
+        self.row_ptr = torch.from_numpy(a.row_ptr.astype(np.int64) if wide else a.row_ptr).to(dev)
         self.col_idx = torch.from_numpy(a.col_idx).to(dev) if a.nnz else torch.zeros(1, dtype=torch.int32, device=dev)
         self.val = torch.from_numpy(a.val).to(dev) if a.nnz else torch.zeros(1, dtype=torch.float64, device=dev)
         self.x = torch.from_numpy(a.x).to(dev) if a.n else torch.zeros(1, dtype=torch.float64, device=dev)
@@ -25,11 +26,11 @@ def convert(d, sigma=0, use_workspace=True, flags=B.CSR5_FLAG_NONE):
     a = d.a
     ws = None
     if use_workspace:
-        nbytes = B.csr5_workspace_bytes(a.m, a.nnz, sigma)
+        nbytes = (B.csr5l_workspace_bytes if d.wide else B.csr5_workspace_bytes)(a.m, a.nnz, sigma)
         assert nbytes > 0
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
         assert ws.data_ptr() % 256 == 0
-    h = B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val, sigma=sigma, workspace=ws,
+    h = (B.csr5l_convert_ex if d.wide else B.csr5_convert_ex)(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val, sigma=sigma, workspace=ws,
                           flags=flags)
     d.workspace = ws
     return h
@@ -46,12 +47,16 @@ def check_format(d, h, label=""):
     assert info["desc_words_per_lane"] == ref.W, label
     st = B.csr5_status(h)
     assert st & 3 == 0, (label, st)
-    tp = B.csr5_read_array(h, B.CSR5_ARRAY_TILE_PTR)
+    tp = B.csr5_read_array(h, B.CSR5_ARRAY_TILE_PTR, wide=d.wide)
+    if d.wide:      # same row indices, flag in bit 63 instead of bit 31, nothing in between
+        assert tp.dtype == np.uint64 and not ((tp >> np.uint64(31)) & np.uint64(0xffffffff)).any(), label
+        tp = ((tp & np.uint64(0x7fffffff)) | ((tp >> np.uint64(63)) << np.uint64(31))).astype(np.uint32)
     assert np.array_equal(tp, ref.tile_ptr), (label, "tile_ptr", _first_diff(tp, ref.tile_ptr))
     assert bool(st & B.CSR5_STATUS_HAS_DIRTY) == bool((ref.tile_ptr >> 31).any()), label
     td = B.csr5_read_array(h, B.CSR5_ARRAY_TILE_DESC)
     assert np.array_equal(td, ref.tile_desc), (label, "tile_desc", _first_diff(td, ref.tile_desc))
-    eop = B.csr5_read_array(h, B.CSR5_ARRAY_EMPTY_OFFSET_PTR)
+    eop = B.csr5_read_array(h, B.CSR5_ARRAY_EMPTY_OFFSET_PTR, wide=d.wide)
+    assert eop.dtype == (np.int64 if d.wide else np.int32)
     assert np.array_equal(eop, ref.empty_offset_ptr), (label, "empty_offset_ptr", _first_diff(eop, ref.empty_offset_ptr))
     assert info["empty_offset_len"] == ref.empty_offset.shape[0], label
     eo = B.csr5_read_array(h, B.CSR5_ARRAY_EMPTY_OFFSET)
@@ -89,3 +94,20 @@ def check_spmv(d, h, label="", x=None):
     empty = np.diff(a.row_ptr) == 0
     assert np.all(y[empty] == 0.0), (label, "empty rows must be exactly zero")
     return float((err / np.maximum(s, 1e-300)).max()) if a.m else 0.0
+
+
+def tile_reference(row_ptr, m, n, t, T, sigma, col_tile, val_tile):
+    """The oracle's conversion of the stand-alone matrix that consists of tile t's
+    entries: rows tile_ptr[t] .. (last row that starts before the tile ends), row
+    boundaries clipped to the tile.  Its only tile has the descriptor, the
+    empty-row flag, the empty_offset entries and the transposed arrays that tile
+    t has inside the big matrix (the forced first flag is what makes the two
+    agree when the tile starts in the middle of a row)."""
+    lo, hi = t * T, (t + 1) * T
+    r0 = int(np.searchsorted(row_ptr, lo, side="right")) - 1
+    r1 = int(np.searchsorted(row_ptr, hi, side="right")) - 1
+    r_end = r1 - 1 if row_ptr[min(r1, m)] == hi else r1
+    rp = (np.clip(row_ptr[r0:r_end + 2], lo, hi) - lo).astype(np.int32)
+    assert rp[0] == 0 and rp[-1] == T
+    ref = oracle.convert(r_end - r0 + 1, n, T, rp, col_tile, val_tile, 64, sigma)
+    return r0, ref

@@ -22,7 +22,7 @@ def lib():
 
 def test_header_symbols_exported(lib):
     hdr = open(os.path.join(ROOT, "include", "csr5.h")).read()
-    declared = set(re.findall(r"\b(csr5s?_[a-z_0-9]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(csr5[sl]?_[a-z_0-9]+)\s*\(", hdr))
     declared -= {"csr5_handle_s"}
     assert declared == set(B.SYMBOLS), declared ^ set(B.SYMBOLS)
     raw = ctypes.CDLL(B.LIB_PATH)
@@ -69,4 +69,26 @@ def test_host_side_argument_errors(lib):
     rc, h = B.csr5_convert_ex(1, 1, 0, 0, 0, 0, check=False, stream=0)
     assert rc == B.CSR5_EINVAL and not h
     assert B.csr5_free(None) == B.CSR5_OK
-    assert B.csr5_strerror(B.CSR5_ERANGE) == "sigma out of range"
+    assert B.csr5_strerror(B.CSR5_ERANGE).startswith("sigma out of range")
+
+
+def test_wide_variant_limits(lib):
+    # 8-byte tile_ptr and empty_offset_ptr entries
+    m, nnz, sigma = 1000, 26000, 16
+    T = 64 * sigma
+    p, pc = -(-nnz // T), nnz // T
+    W = oracle.desc_words(64, sigma)
+    need = (p + 1) * 8 + pc * W * 64 * 4 + (pc + 1) * 8 + min(m + pc, pc * T) * 4 + (p + 1) * 8 + 4
+    got = B.csr5l_workspace_bytes(m, nnz, sigma)
+    assert need <= got <= need + 6 * 256
+    # beyond 2^31 nonzeros; the limit is the number of tiles (2^26 - 5)
+    assert B.csr5l_workspace_bytes(6_400_000, 2_300_000_000, 16) > 2_300_000_000 // 1024 * 64 * 4
+    most = (2**26 - 5) * 64 * 16
+    assert B.csr5l_workspace_bytes(1000, most, 16) > 0
+    assert B.csr5l_workspace_bytes(1000, most + 1, 16) == 0
+    assert B.csr5l_workspace_bytes(1000, most, 15) == 0
+    # the conversion refuses such a matrix before touching any pointer (dummy addresses)
+    rc, h = B.csr5l_convert_ex(1000, 1000, most + 1, 256, 256, 256, sigma=16, check=False, stream=0)
+    assert rc == B.CSR5_ERANGE and not h
+    rc, h = B.csr5l_convert_ex(1000, 1000, 100, 260, 256, 256, sigma=16, check=False, stream=0)
+    assert rc == B.CSR5_EINVAL and not h          # int64 row_ptr must be 8-byte aligned
