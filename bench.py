@@ -28,12 +28,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
 
-def bytes_model(a, info, n_ref, vb=8):
+def bytes_model(m, nnz, info, n_ref, vb=8, ib=4):
     """Algorithmic bytes of one SpMV: val + col_idx (vb + 4 B per nonzero), packed
     descriptors, tile_ptr, empty_offset and its per-tile starts, every
-    referenced x entry once, y written once.  vb = bytes per value (8 or 4)."""
+    referenced x entry once, y written once.  vb = bytes per value (8 or 4),
+    ib = bytes per tile_ptr / empty_offset_ptr entry (8 in the 64-bit index variant)."""
     W, p, pc, E = info["desc_words_per_lane"], info["p"], info["p_complete"], info["empty_offset_len"]
-    return ((vb + 4) * a.nnz + 4 * W * 64 * pc + 4 * (p + 1) + 4 * (pc + 1) + 4 * E + vb * n_ref + vb * a.m)
+    return ((vb + 4) * nnz + 4 * W * 64 * pc + ib * (p + 1) + ib * (pc + 1) + 4 * E + vb * n_ref + vb * m)
 
 
 def main():
@@ -41,7 +42,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: the 27-point stencil)")
+    ap.add_argument("--workload", type=int, default=2,
+                    help="1..6 (default 2: the 27-point stencil); 7 = the 2.2e9-nonzero matrix of the "
+                         "64-bit index variant, generated in GPU memory")
     ap.add_argument("--sigma", type=int, default=0, help="tile height, 0 = the library's rule")
     ap.add_argument("--dtype", choices=["f64", "f32"], default="f64",
                     help="f64 is the headline; f32 runs the single-precision instantiation")
@@ -86,22 +89,45 @@ def main():
     spmv_ex = B.csr5s_spmv_ex if f32 else B.csr5_spmv_ex
     spmv_profile = B.csr5s_spmv_profile if f32 else B.csr5_spmv_profile
 
-    a = wl.config(args.workload)
-    if f32:
-        a.val = a.val.astype(np.float32)
-        a.x = a.x.astype(np.float32)
-    st = a.stats()
-    n_ref = int(np.unique(a.col_idx).size)
-    row_ptr = torch.from_numpy(a.row_ptr).to(dev)
-    col0 = torch.from_numpy(a.col_idx).to(dev)        # pristine CSR copies
-    val0 = torch.from_numpy(a.val).to(dev)
+    wide = args.workload == 7
+    if wide:
+        if f32:
+            print("bench.py: the 64-bit index variant is double precision only", file=sys.stderr)
+            sys.exit(2)
+        from paper_1503_05032_amd import workloads_device as wd
+        A = wd.huge_mixed(dev)
+        a = None
+        m, n, nnz, name = A["m"], A["n"], A["nnz"], A["name"]
+        row_ptr, col0, val0, x = A["row_ptr"], A["col_idx"], A["val"], A["x"]
+        row_ptr_h = row_ptr.cpu().numpy()
+        lens = np.diff(row_ptr_h)
+        st = {"row_len_min": int(lens.min()), "row_len_avg": float(lens.mean()), "row_len_max": int(lens.max()),
+              "empty_rows": int((lens == 0).sum())}
+        seen = torch.zeros(n, dtype=torch.bool, device=dev)
+        for e0 in range(0, nnz, 1 << 28):
+            seen[col0[e0:e0 + (1 << 28)].long()] = True
+        n_ref = int(seen.sum().item())
+        del seen
+        convert_ex, workspace_bytes = B.csr5l_convert_ex, B.csr5l_workspace_bytes
+    else:
+        a = wl.config(args.workload)
+        if f32:
+            a.val = a.val.astype(np.float32)
+            a.x = a.x.astype(np.float32)
+        m, n, nnz, name = a.m, a.n, a.nnz, a.name
+        st = a.stats()
+        n_ref = int(np.unique(a.col_idx).size)
+        row_ptr = torch.from_numpy(a.row_ptr).to(dev)
+        col0 = torch.from_numpy(a.col_idx).to(dev)        # pristine CSR copies
+        val0 = torch.from_numpy(a.val).to(dev)
+        x = torch.from_numpy(a.x).to(dev)
+        workspace_bytes = B.csr5_workspace_bytes
     col = col0.clone()
     val = val0.clone()
-    x = torch.from_numpy(a.x).to(dev)
-    y = torch.empty(a.m, dtype=tdt, device=dev)
+    y = torch.empty(m, dtype=tdt, device=dev)
 
-    sigma = args.sigma or B.csr5_sigma_auto(a.nnz, a.m)
-    ws = torch.empty(B.csr5_workspace_bytes(a.m, a.nnz, sigma), dtype=torch.uint8, device=dev)
+    sigma = args.sigma or B.csr5_sigma_auto(nnz, m)
+    ws = torch.empty(workspace_bytes(m, nnz, sigma), dtype=torch.uint8, device=dev)
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
@@ -118,7 +144,7 @@ def main():
         torch.cuda.synchronize()
         e0, e1 = ev(), ev()
         e0.record()
-        h = convert_ex(a.m, a.n, a.nnz, row_ptr, col, val, sigma=sigma, workspace=ws,
+        h = convert_ex(m, n, nnz, row_ptr, col, val, sigma=sigma, workspace=ws,
                        flags=B.CSR5_FLAG_NO_HOST_CHECK)
         e1.record()
         torch.cuda.synchronize()
@@ -128,7 +154,7 @@ def main():
             c2, v2 = col0.clone(), val0.clone()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            h2 = convert_ex(a.m, a.n, a.nnz, row_ptr, c2, v2, sigma=sigma)
+            h2 = convert_ex(m, n, nnz, row_ptr, c2, v2, sigma=sigma)
             torch.cuda.synchronize()
             conv_alloc_ms.append((time.perf_counter() - t0) * 1e3)
             B.csr5_free(h2)
@@ -141,8 +167,18 @@ def main():
     import oracle
     spmv_ex(h, x, y)
     torch.cuda.synchronize()
-    y_ref, s_abs = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val.astype(np.float64), a.x.astype(np.float64))
-    err = np.abs(y.cpu().numpy().astype(np.float64) - y_ref)
+    if wide:
+        # the oracle on a sample of rows (random ones, the longest ones, the first and the last)
+        rng = np.random.default_rng(11)
+        rows_s = np.unique(np.concatenate([rng.integers(0, m, 400), np.argsort(lens)[-8:], [0, m - 1]]))
+        cs = np.concatenate([col0[row_ptr_h[r]:row_ptr_h[r + 1]].cpu().numpy() for r in rows_s])
+        vs = np.concatenate([val0[row_ptr_h[r]:row_ptr_h[r + 1]].cpu().numpy() for r in rows_s])
+        rp_s = np.concatenate([[0], np.cumsum(lens[rows_s])]).astype(np.int32)
+        y_ref, s_abs = oracle.csr_spmv(len(rows_s), rp_s, cs, vs, x.cpu().numpy())
+        err = np.abs(y[torch.from_numpy(rows_s).to(dev)].cpu().numpy() - y_ref)
+    else:
+        y_ref, s_abs = oracle.csr_spmv(m, a.row_ptr, a.col_idx, a.val.astype(np.float64), a.x.astype(np.float64))
+        err = np.abs(y.cpu().numpy().astype(np.float64) - y_ref)
     parity_ok = bool(np.all(err <= (1e-5 if f32 else 1e-12) * s_abs + (1e-30 if f32 else 1e-300)))
 
     # ---------------------------------------------------------------- timed region: exactly K steps
@@ -158,9 +194,9 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = e0.elapsed_time(e1) / args.steps
-    gflops = 2.0 * a.nnz / (ms_per_step * 1e-3) / 1e9
-    B_model = bytes_model(a, info, n_ref, vb)
-    B_gather = B_model - vb * n_ref + vb * a.nnz
+    gflops = 2.0 * nnz / (ms_per_step * 1e-3) / 1e9
+    B_model = bytes_model(m, nnz, info, n_ref, vb, 8 if wide else 4)
+    B_gather = B_model - vb * n_ref + vb * nnz
 
     extras = {}
     if not args.quick:
@@ -208,10 +244,11 @@ def main():
         "dtype": args.dtype,
         "data": "synthetic",
         "config": {
-            "workload": f"configs[{args.workload - 1}] {a.name}: {a.m}x{a.n}, nnz={a.nnz}, "
+            "workload": (f"configs[{args.workload - 1}]" if args.workload <= 5 else f"extra workload {args.workload}")
+                        + f" {name}: {m}x{n}, nnz={nnz}, "
                         f"nnz/row min/avg/max={st['row_len_min']}/{st['row_len_avg']:.2f}/{st['row_len_max']}, "
                         f"empty rows={st['empty_rows']}",
-            "omega": 64, "sigma": info["sigma"], "tiles": info["p"],
+            "omega": 64, "sigma": info["sigma"], "tiles": info["p"], "index_bits": 64 if wide else 32,
             "desc_words_per_lane": info["desc_words_per_lane"],
             "empty_offset_len": info["empty_offset_len"],
         },
@@ -248,18 +285,28 @@ def main():
     if not args.no_cpu_baseline:
         # the oracle as it stands (sequential Algorithm 1, one core), repeated on the
         # same matrix until about cpu_seconds of work
+        if wide:      # a bounded part of the matrix: its first rows, about 3e7 nonzeros
+            m_s = int(np.searchsorted(row_ptr_h, 30_000_000))
+            nnz_s = int(row_ptr_h[m_s])
+            o_args = (m_s, row_ptr_h[:m_s + 1].astype(np.int32), col0[:nnz_s].cpu().numpy(),
+                      val0[:nnz_s].cpu().numpy(), x.cpu().numpy())
+            what = f"SpMVs of the first {m_s} rows ({nnz_s} nonzeros) of the same matrix"
+        else:
+            nnz_s = nnz
+            o_args = (m, a.row_ptr, a.col_idx, a.val, a.x)             # the oracle computes in fp64
+            what = "full SpMVs of the same matrix"
         reps, t_acc = 0, 0.0
         while t_acc < args.cpu_seconds and reps < 2000:
             t0 = time.perf_counter()
-            oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)      # the oracle computes in fp64
+            oracle.csr_spmv(*o_args)
             t_acc += time.perf_counter() - t0
             reps += 1
         out["cpu_baseline"] = {
-            "value": round(2.0 * a.nnz * reps / t_acc / 1e9, 3),
+            "value": round(2.0 * nnz_s * reps / t_acc / 1e9, 3),
             "unit": "GFLOP/s",
             "cores": 1,
             "kind": "oracle",
-            "sample": f"{reps} full SpMVs of the same matrix (sequential Algorithm 1, gcc -O2), "
+            "sample": f"{reps} {what} (sequential Algorithm 1, gcc -O2), "
                       f"{t_acc:.1f} s of CPU time; host has {os.cpu_count()} logical CPUs",
         }
 

@@ -71,8 +71,9 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * nnz nonzeros at the given sigma (0 = the value csr5_sigma_auto picks).  An
  * upper bound computable on the host: tile_ptr (p+1 words) + tile_desc
  * (p_c*W*64 words) + empty_offset_ptr (p_c+1 words) + empty_offset (at most
- * min(m + p_c, p_c*T) words) + the SpMV's auxiliary array (p+1 doubles) + a
- * status word, each rounded up to 256 bytes.
+ * min(m + p_c, p_c*T) words) + the SpMV's auxiliary array (p+1 doubles) + the
+ * conversion's scan scratch (p_c/8192 + 1 words) + a status word, each rounded
+ * up to 256 bytes.
  * Returns 0 for invalid arguments.
  */
 size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma);

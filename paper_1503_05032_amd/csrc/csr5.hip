@@ -103,6 +103,13 @@ __device__ __forceinline__ int count_le_tileptr(const typename Index<IT>::tp_t* 
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (OMEGA - 1); }
 
+// Sets a bit of the status word.  Hundreds of thousands of threads may want the
+// same bit, and atomics on one address are served one after the other, so look
+// first: after the first few, everybody finds it set.
+__device__ __forceinline__ void raise_status(uint32_t* status, uint32_t bit) {
+    if (!(__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(status, bit);
+}
+
 // Native global floating-point atomic add (fp64 or fp32), no return value.
 template <typename VT>
 __device__ __forceinline__ void atomic_add_fp(VT* addr, VT v) {
@@ -162,16 +169,16 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
     IT a = row_ptr[r], b = row_ptr[r + 1];
     bool bad = (a < 0) || (b < a) || (b > nnz) || (r == 0 && a != 0) || (r == m - 1 && b != nnz);
     if (bad) {
-        atomicOr(status, CSR5_STATUS_BAD_ROW_PTR);
+        raise_status(status, CSR5_STATUS_BAD_ROW_PTR);
         return;
     }
     if (a == b) {
         // one flag write per wavefront is enough: the lowest lane that sees an empty row
-        if (lane_id() == __builtin_ctzll(__ballot(1))) atomicOr(status, CSR5_STATUS_HAS_EMPTY_ROWS);
+        if (lane_id() == __builtin_ctzll(__ballot(1))) raise_status(status, CSR5_STATUS_HAS_EMPTY_ROWS);
         int t = count_le_tileptr<IT>(tile_ptr, p + 1, uint32_t(r)) - 1;
         if (t >= 0 && t < p) {
             tp_t old = __hip_atomic_fetch_or(&tile_ptr[t], DIRTY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (!(old & DIRTY)) atomicOr(status, CSR5_STATUS_HAS_DIRTY);
+            if (!(old & DIRTY)) raise_status(status, CSR5_STATUS_HAS_DIRTY);
         }
     } else if (int64_t(a) < int64_t(pc) * T) {
         int tile = int(a / T);
@@ -225,10 +232,61 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
 
 // ----------------------------------------------------------------------------
 // empty_offset layout: exclusive prefix sum of the per-tile segment counts
-// (non-zero only for tiles with an empty row).  One workgroup; the array has
-// p_c + 1 entries.  Skipped when no tile is marked.
+// (non-zero only for tiles with an empty row); the array has p_c + 1 entries.
+// Nothing to scan when no tile is marked.  Up to SCAN_SINGLE tiles one workgroup
+// walks the array chunk by chunk; beyond that every chunk gets a workgroup
+// (local scan + chunk total), one workgroup scans the chunk totals, and a third
+// launch adds them back.
 // ----------------------------------------------------------------------------
-constexpr int SCAN_THREADS = 1024, SCAN_ITEMS = 8;
+constexpr int SCAN_THREADS = 1024, SCAN_ITEMS = 8, SCAN_CHUNK = SCAN_THREADS * SCAN_ITEMS;
+constexpr int SCAN_SINGLE = 8 * SCAN_CHUNK;
+
+// Exclusive scan of a[base .. base + SCAN_CHUNK) (entries at or beyond len count
+// as 0) by one workgroup of SCAN_THREADS threads, in place, plus `carry`;
+// returns the chunk's total to every thread.
+template <typename IT>
+__device__ IT scan_chunk(IT* __restrict__ a, int64_t base, int64_t len, IT carry) {
+    __shared__ IT wave_sum[SCAN_THREADS / OMEGA];
+    __shared__ IT chunk_total;
+    const int lane = lane_id(), wave = threadIdx.x / OMEGA;
+    const int64_t idx0 = base + int64_t(threadIdx.x) * SCAN_ITEMS;
+    IT local[SCAN_ITEMS];
+    IT s = 0;
+#pragma unroll
+    for (int q = 0; q < SCAN_ITEMS; q++) {
+        IT v = (idx0 + q < len) ? a[idx0 + q] : IT(0);
+        local[q] = s;
+        s += v;
+    }
+    IT incl = s;
+#pragma unroll
+    for (int d = 1; d < OMEGA; d <<= 1) {
+        IT up = __shfl_up(incl, d, OMEGA);
+        if (lane >= d) incl += up;
+    }
+    if (lane == OMEGA - 1) wave_sum[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        IT v = (lane < SCAN_THREADS / OMEGA) ? wave_sum[lane] : IT(0);
+        IT ws = v;
+#pragma unroll
+        for (int d = 1; d < SCAN_THREADS / OMEGA; d <<= 1) {
+            IT up = __shfl_up(ws, d, OMEGA);
+            if (lane >= d) ws += up;
+        }
+        if (lane < SCAN_THREADS / OMEGA) wave_sum[lane] = ws - v;  // exclusive
+        if (lane == SCAN_THREADS / OMEGA - 1) chunk_total = ws;
+    }
+    __syncthreads();
+    const IT excl = carry + wave_sum[wave] + incl - s;
+#pragma unroll
+    for (int q = 0; q < SCAN_ITEMS; q++)
+        if (idx0 + q < len) a[idx0 + q] = excl + local[q];
+    const IT total = chunk_total;
+    __syncthreads();                                    // the shared words are reused by the next call
+    return total;
+}
+
 template <typename IT>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_eop(int pc, IT* __restrict__ eop, const uint32_t* __restrict__ status) {
@@ -236,48 +294,40 @@ k_scan_eop(int pc, IT* __restrict__ eop, const uint32_t* __restrict__ status) {
         if (threadIdx.x == 0) eop[pc] = 0;
         return;
     }
-    __shared__ IT wave_sum[SCAN_THREADS / OMEGA];
-    __shared__ IT chunk_total;
-    int lane = lane_id(), wave = threadIdx.x / OMEGA;
     IT carry = 0;
-    for (int64_t base = 0; base < pc; base += SCAN_THREADS * SCAN_ITEMS) {
-        int64_t idx0 = base + threadIdx.x * SCAN_ITEMS;
-        IT local[SCAN_ITEMS];
-        IT s = 0;
-#pragma unroll
-        for (int q = 0; q < SCAN_ITEMS; q++) {
-            IT v = (idx0 + q < pc) ? eop[idx0 + q] : IT(0);
-            local[q] = s;
-            s += v;
-        }
-        IT incl = s;
-#pragma unroll
-        for (int d = 1; d < OMEGA; d <<= 1) {
-            IT up = __shfl_up(incl, d, OMEGA);
-            if (lane >= d) incl += up;
-        }
-        if (lane == OMEGA - 1) wave_sum[wave] = incl;
-        __syncthreads();
-        if (wave == 0) {
-            IT v = (lane < SCAN_THREADS / OMEGA) ? wave_sum[lane] : IT(0);
-            IT ws = v;
-#pragma unroll
-            for (int d = 1; d < SCAN_THREADS / OMEGA; d <<= 1) {
-                IT up = __shfl_up(ws, d, OMEGA);
-                if (lane >= d) ws += up;
-            }
-            if (lane < SCAN_THREADS / OMEGA) wave_sum[lane] = ws - v;  // exclusive
-            if (lane == SCAN_THREADS / OMEGA - 1) chunk_total = ws;
-        }
-        __syncthreads();
-        IT excl = carry + wave_sum[wave] + incl - s;
-#pragma unroll
-        for (int q = 0; q < SCAN_ITEMS; q++)
-            if (idx0 + q < pc) eop[idx0 + q] = excl + local[q];
-        carry += chunk_total;
-        __syncthreads();
-    }
+    for (int64_t base = 0; base < pc; base += SCAN_CHUNK) carry += scan_chunk(eop, base, int64_t(pc), carry);
     if (threadIdx.x == 0) eop[pc] = carry;
+}
+
+// large arrays, step 1: workgroup b scans chunk b on its own
+template <typename IT>
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_scan_chunks(int pc, IT* __restrict__ eop, IT* __restrict__ chunk_sum, const uint32_t* __restrict__ status) {
+    if (!(*status & CSR5_STATUS_HAS_DIRTY)) return;
+    IT total = scan_chunk(eop, int64_t(blockIdx.x) * SCAN_CHUNK, int64_t(pc), IT(0));
+    if (threadIdx.x == 0) chunk_sum[blockIdx.x] = total;
+}
+
+// step 2: one workgroup scans the chunk totals (at most SCAN_CHUNK of them)
+template <typename IT>
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_scan_chunk_sums(int pc, int nchunks, IT* __restrict__ eop, IT* __restrict__ chunk_sum,
+                  const uint32_t* __restrict__ status) {
+    if (!(*status & CSR5_STATUS_HAS_DIRTY)) {
+        if (threadIdx.x == 0) eop[pc] = 0;
+        return;
+    }
+    IT total = scan_chunk(chunk_sum, 0, int64_t(nchunks), IT(0));
+    if (threadIdx.x == 0) eop[pc] = total;
+}
+
+// step 3: add every chunk's offset
+template <typename IT>
+__global__ void __launch_bounds__(256)
+k_scan_add(int pc, IT* __restrict__ eop, const IT* __restrict__ chunk_sum, const uint32_t* __restrict__ status) {
+    if (!(*status & CSR5_STATUS_HAS_DIRTY)) return;
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < pc) eop[i] += chunk_sum[i / SCAN_CHUNK];
 }
 
 // ----------------------------------------------------------------------------
@@ -440,7 +490,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
             bad |= (ce < 0) | (ce >= n);
         }
     }
-    if (!BACK && bad) atomicOr(status, CSR5_STATUS_BAD_COL_IDX);
+    if (!BACK && bad) raise_status(status, CSR5_STATUS_BAD_COL_IDX);
 }
 
 // ----------------------------------------------------------------------------
@@ -876,7 +926,7 @@ struct csr5_handle_s {
 namespace {
 
 struct Layout {
-    size_t off_tile_ptr, off_desc, off_eop, off_eo, off_carry, off_status, total;
+    size_t off_tile_ptr, off_desc, off_eop, off_eo, off_carry, off_scan, off_status, total;
     size_t ndesc, eo_cap;
 };
 
@@ -893,6 +943,7 @@ Layout make_layout(int32_t m, const Geom& g, bool wide) {
     L.off_eop = o;      o += align256((size_t(g.pc) + 1) * isz);
     L.off_eo = o;       o += align256(L.eo_cap * 4);
     L.off_carry = o;    o += align256((size_t(g.p) + 1) * 8);
+    L.off_scan = o;     o += align256((size_t(g.pc) / SCAN_CHUNK + 1) * isz);   // chunk totals of the scan
     L.off_status = o;   o += 256;
     L.total = o;
     return L;
@@ -1030,8 +1081,17 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
                            g.ybits, g.pc, tile_ptr, h->tile_desc, eop);
         e = hipGetLastError();
     }
-    if (e == hipSuccess) {
+    if (e == hipSuccess && g.pc <= SCAN_SINGLE) {
         hipLaunchKernelGGL(k_scan_eop<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, eop, h->status);
+        e = hipGetLastError();
+    } else if (e == hipSuccess) {
+        IT* chunk_sum = reinterpret_cast<IT*>(basep + L.off_scan);
+        const int nchunks = (g.pc + SCAN_CHUNK - 1) / SCAN_CHUNK;      // <= 2^26 / 2^13
+        hipLaunchKernelGGL(k_scan_chunks<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, eop, chunk_sum, h->status);
+        hipLaunchKernelGGL(k_scan_chunk_sums<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, nchunks, eop, chunk_sum,
+                           h->status);
+        hipLaunchKernelGGL(k_scan_add<IT>, dim3(uint32_t((size_t(g.pc) + 255) / 256)), dim3(256), 0, s, g.pc, eop,
+                           chunk_sum, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && g.pc > 0 && m > 0) {

@@ -85,6 +85,21 @@ def test_full_size_configs(cfg):
     B.csr5_free(h)
 
 
+@pytest.mark.parametrize("sigma,wide", [(4, False), (2, True)])
+def test_many_marked_tiles(sigma, wide):
+    """More than 65536 tiles, a third of them holding empty rows: the layout of
+    empty_offset is then scanned by many workgroups instead of one."""
+    a = wl.config(4)
+    d = DeviceCsr(a, wide=wide)
+    h = convert(d, sigma=sigma)
+    info = B.csr5_get_info(h)
+    say("tiles", info["p"], "empty_offset_len", info["empty_offset_len"])
+    assert info["p_complete"] > 65536 and info["empty_offset_len"] > 0
+    check_format(d, h, ("many marked tiles", sigma, wide))
+    check_spmv(d, h, ("many marked tiles", sigma, wide))
+    B.csr5_free(h)
+
+
 def test_workspace_and_malloc_paths_agree():
     a = wl.config(3, scale=0.02)
     d1, d2 = DeviceCsr(a), DeviceCsr(a)
