@@ -29,7 +29,7 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, no fast-math).  Returns the .so path."""
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
         tmp = _SO + f".tmp{os.getpid()}"
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-shared", "-fPIC",
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-fopenmp", "-shared", "-fPIC",
                                "-o", tmp, _SRC])
         os.replace(tmp, _SO)
     return _SO
@@ -57,6 +57,7 @@ def lib():
                      "oracle_pack_desc", "oracle_empty_offset", "oracle_transpose",
                      "oracle_csr5_spmv"):
             getattr(_lib, name).restype = None
+        _lib.oracle_csr_spmv_all_cores.restype = C.c_int32
     return _lib
 
 
@@ -77,6 +78,18 @@ def csr_spmv(m, row_ptr, col_idx, val, x):
                           _p(val, C.c_double), _p(x, C.c_double), _p(y, C.c_double),
                           _p(s, C.c_double))
     return y, s
+
+
+def csr_spmv_all_cores(m, row_ptr, col_idx, val, x):
+    """Algorithm 1 with the rows shared among the host's cores (OpenMP); the same
+    values as csr_spmv.  Returns (y, abs_sum, threads used)."""
+    row_ptr, col_idx, val, x = _i32(row_ptr), _i32(col_idx), _f64(val), _f64(x)
+    y = np.empty(m, dtype=np.float64)
+    s = np.empty(m, dtype=np.float64)
+    nt = lib().oracle_csr_spmv_all_cores(C.c_int32(m), _p(row_ptr, C.c_int32), _p(col_idx, C.c_int32),
+                                         _p(val, C.c_double), _p(x, C.c_double), _p(y, C.c_double),
+                                         _p(s, C.c_double))
+    return y, s, int(nt)
 
 
 def num_tiles(nnz, omega, sigma):

@@ -40,6 +40,30 @@ void oracle_csr_spmv(int32_t m, const int32_t *row_ptr, const int32_t *col_idx,
     }
 }
 
+/* The same rows by the same loop, rows shared among the host's cores (each row is
+ * still summed sequentially in CSR order, so the result is bit-identical to
+ * oracle_csr_spmv).  Exists for the benchmark's all-cores CPU figure only.
+ * Returns the number of threads that took part. */
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+int32_t oracle_csr_spmv_all_cores(int32_t m, const int32_t *row_ptr, const int32_t *col_idx,
+                                  const double *val, const double *x, double *y, double *abs_sum)
+{
+    int32_t threads = 1;
+#pragma omp parallel
+    {
+#ifdef _OPENMP
+#pragma omp single
+        threads = omp_get_num_threads();
+#endif
+#pragma omp for schedule(dynamic, 1024)
+        for (int32_t i = 0; i < m; i++)
+            oracle_csr_spmv(1, row_ptr + i, col_idx, val, x, y + i, abs_sum ? abs_sum + i : 0);
+    }
+    return threads;
+}
+
 /* The "binary_search" of Algorithms 4 and 7 is not defined in the paper.  With
  * empty rows several row_ptr entries are equal, so it is read as an upper
  * bound: the number of entries of row_ptr[0..m] that are <= key.  Minus one,

@@ -333,7 +333,8 @@ def dense(n=2000, seed=5) -> Csr:
 # registry of the five headline workloads and their scaled-down versions
 # --------------------------------------------------------------------------
 def config(i: int, scale: float = 1.0) -> Csr:
-    """Workload i in 1..5 (6 = the paper's dense 2K x 2K matrix) at full size
+    """Workload i in 1..5 (6 = the paper's dense 2K x 2K matrix, 8 = the smaller
+    variant of workload 4; 7 lives in workloads_device) at full size
     (scale=1) or shrunk (scale<1 reduces the number of rows; the per-row
     distributions are unchanged)."""
     if i == 1:
@@ -353,6 +354,12 @@ def config(i: int, scale: float = 1.0) -> Csr:
         return mixed_large(m=m, band=min(5000, m // 4), chunk_rows=1_000_000)
     if i == 6:                      # extra: the paper's own dense matrix
         return dense(max(64, int(round(2000 * scale ** 0.5))))
+    if i == 8:                      # extra: config 4 with 0.026 % dense rows, which meets its stated "~12 M" nonzeros
+        m = max(1000, int(1_500_000 * scale))
+        nn = max(2000, int(4_000_000 * scale))
+        a = lp_rect(m=m, n=nn, dense_frac=0.00026, dense_len=min(20_000, nn // 4))
+        a.name += "_b"
+        return a
     raise ValueError(i)
 
 

@@ -70,7 +70,7 @@ def test_config1_auto_sigma_and_plain_convert():
     B.csr5_free(h)
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4, 5, 6])
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5, 6, 8])
 def test_full_size_configs(cfg):
     say("generating config", cfg)
     a = wl.config(cfg)

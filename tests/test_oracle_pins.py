@@ -321,3 +321,13 @@ def test_csr5_spmv_mid_size():
         y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
         y5 = oracle.csr5_spmv(c5, a.x)
         assert np.all(np.abs(y5 - y_ref) <= 1e-12 * s + 1e-300)
+
+
+def test_all_cores_variant_is_bit_identical():
+    """The OpenMP loop of the benchmark's all-cores figure sums every row exactly as Algorithm 1 does."""
+    a = wl.config(3, scale=0.01)
+    y1, s1 = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
+    y2, s2, threads = oracle.csr_spmv_all_cores(a.m, a.row_ptr, a.col_idx, a.val, a.x)
+    assert threads >= 1
+    assert np.array_equal(y1.view(np.uint64), y2.view(np.uint64))
+    assert np.array_equal(s1.view(np.uint64), s2.view(np.uint64))

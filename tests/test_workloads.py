@@ -59,7 +59,7 @@ def test_stencil_small_and_full_nnz_formula():
     assert all((c, r) in allp for r, c in fwd)
 
 
-@pytest.mark.parametrize("cfg,scale", [(3, 0.02), (4, 0.02), (5, 0.01)])
+@pytest.mark.parametrize("cfg,scale", [(3, 0.02), (4, 0.02), (5, 0.01), (8, 0.05)])
 def test_scaled_irregular_workloads(cfg, scale):
     a = wl.config(cfg, scale=scale)
     check_structure(a)
@@ -71,6 +71,9 @@ def test_scaled_irregular_workloads(cfg, scale):
     if cfg == 4:
         assert 0.27 < (lens == 0).mean() < 0.33
         assert lens.max() > 1000
+    if cfg == 8:      # same row model with a quarter of the dense rows: 12 M nonzeros at full size
+        assert 0.27 < (lens == 0).mean() < 0.33
+        assert 6.5 < lens.mean() < 9.0 and lens.max() > 1000
     if cfg == 5:
         assert lens.min() >= 1 and 12.0 < lens.mean() < 22.0
     assert digest(a) == digest(wl.config(cfg, scale=scale))
