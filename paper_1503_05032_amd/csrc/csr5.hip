@@ -503,9 +503,9 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
 // stored straight to y[tile_ptr + y_offset + k].  What follows the last flag is
 // the "blue" tail.
 //
-// In-tile segmented sum (Algorithm 8 line 22).  Algorithm 6 computes it as a
-// difference of two prefix sums over the whole tile, which loses the accuracy
-// of a small row sitting after large ones.  Here: red partials are shifted one
+// In-tile segmented sum (the step of Algorithm 8 that calls Algorithm 6).
+// Algorithm 6 computes it as a difference of two prefix sums over the whole
+// tile, which loses the accuracy of a small row sitting after large ones.  Here: red partials are shifted one
 // lane down (tmp[i] = red[i+1], the printed tmp[i-1] <- sum) and summed by a
 // segmented suffix scan made of six wavefront shuffles, the segments being
 // delimited by the ballot of "column has a flag".  The range it sums for a head
@@ -558,8 +558,9 @@ __device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
     const int span = int(nnz - first);                   // < one tile
     const int nchunks = (span + OMEGA - 1) / OMEGA;
     for (int q = wave; q < nchunks && q < TAIL_MAX_CHUNKS; q += nwaves) {
-        const IT chunk_lo = first + q * OMEGA;
-        const IT e = chunk_lo + lane;
+        // 64-bit: with 32-bit indices and nnz within 64 of 2^31 these would overflow
+        const int64_t chunk_lo = int64_t(first) + q * OMEGA;
+        const int64_t e = chunk_lo + lane;
         const bool live = e < nnz;
         int row = -2 - lane;                         // distinct keys for dead lanes
         VT prod = VT(0);
@@ -661,7 +662,7 @@ k_spmv(int m, IT nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     const flag_t flags = flag_t(lo) & FLAG_MASK;
     uint32_t yo = uint32_t(lo >> YSH);
     if (W > 2) yo |= uint32_t(hi << (64 - YSH));
-    // empty_offset slice of a tile that holds empty rows (Algorithm 8 line 4)
+    // empty_offset slice of a tile that holds empty rows (Algorithm 8, where y_offset is replaced by empty_offset[y_offset])
     const int32_t* eo_t = nullptr;
     uint32_t nseg_t = 0;
     if (dirty) {
@@ -886,7 +887,7 @@ k_csr_vector(int m, const int32_t* __restrict__ row_ptr, const int32_t* __restri
     const int sub = int(gid % LANES);
     double acc = 0.0;
     if (r < int64_t(m))
-        for (int k = row_ptr[r] + sub, e = row_ptr[r + 1]; k < e; k += LANES)
+        for (int64_t k = int64_t(row_ptr[r]) + sub, e = row_ptr[r + 1]; k < e; k += LANES)
             acc = fma(val[k], x[col_idx[k]], acc);
 #pragma unroll
     for (int d = LANES / 2; d >= 1; d >>= 1) acc += __shfl_down(acc, d, LANES);

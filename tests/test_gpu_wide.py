@@ -213,3 +213,69 @@ def test_wide_more_than_2g_nonzeros():
         assert torch.equal(col[e0:e1], col0[e0:e1]) and torch.equal(val[e0:e1], val0[e0:e1])
     B.csr5_free(h)
     say(f"done in {time.time() - t_start:.1f}s")
+
+
+def test_int32_variant_at_its_largest_size():
+    """nnz = 2^31 - 1 through the 32-bit entry points: the first rows of the large
+    matrix, the last row cut so that the count is exact.  1023 entries follow the
+    last complete tile, so the incomplete-tile path works right below the top of
+    the index range."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 90 * 2**30:
+        pytest.skip("needs about 80 GB of GPU memory")
+    dev = torch.device("cuda:0")
+    A = wd.huge_mixed(dev)
+    nnz = 2**31 - 1
+    rp64 = A["row_ptr"]
+    m = int(torch.searchsorted(rp64, torch.tensor([nnz], device=dev), right=True).item())   # rows 0..m-1 start at or before nnz
+    rp64 = rp64[:m + 1].clone()
+    rp64[m] = nnz                                        # the last row ends where int32 ends
+    if int(rp64[m - 1].item()) == nnz:
+        m -= 1
+        rp64 = rp64[:m + 1]
+    n = A["n"]
+    row_ptr_d = rp64.to(torch.int32)
+    col, val, x = A["col_idx"][:nnz].clone(), A["val"][:nnz].clone(), A["x"]
+    col0, val0 = A["col_idx"], A["val"]                 # CSR order (the clones get transposed)
+    row_ptr = row_ptr_d.cpu().numpy()
+    lens = np.diff(row_ptr.astype(np.int64))
+    say("m", m, "nnz", nnz, "last row length", int(lens[-1]))
+    sigma = 16
+    T = 64 * sigma
+    p, pc = (nnz + T - 1) // T, nnz // T
+    assert nnz - pc * T == 1023
+    ws = torch.empty(B.csr5_workspace_bytes(m, nnz, sigma), dtype=torch.uint8, device=dev)
+    h = B.csr5_convert_ex(m, n, nnz, row_ptr_d, col, val, sigma=sigma, workspace=ws)     # blocking, with the checks
+    assert B.csr5_status(h) & 3 == 0
+    tp = B.csr5_read_array(h, B.CSR5_ARRAY_TILE_PTR)
+    rows = (tp & np.uint32(0x7fffffff)).astype(np.int64)
+    bnd = np.arange(p + 1, dtype=np.int64) * T
+    assert rows[p] == m and np.all(row_ptr[rows] <= bnd)
+    assert np.all((row_ptr[np.minimum(rows + 1, m)] > bnd) | (rows >= m))
+    rng = np.random.default_rng(3)
+    td = B.csr5_read_array(h, B.CSR5_ARRAY_TILE_DESC).reshape(pc, -1)
+    rp_wide = row_ptr.astype(np.int64)
+    for t in sorted(set(rng.integers(0, pc, 40).tolist()) | {0, pc - 1, pc - 2}):
+        lo, hi = t * T, (t + 1) * T
+        r0, ref = tile_reference(rp_wide, m, n, t, T, sigma, col0[lo:hi].cpu().numpy(), val0[lo:hi].cpu().numpy())
+        assert r0 == rows[t] and np.array_equal(td[t], ref.tile_desc), t
+        assert np.array_equal(col[lo:hi].cpu().numpy(), ref.col_idx), t
+    y = torch.full((m,), float("nan"), dtype=torch.float64, device=dev)
+    B.csr5_spmv_ex(h, x, y)
+    torch.cuda.synchronize()
+    rows_s = np.unique(np.concatenate([rng.integers(0, m, 200), np.arange(m - 40, m), np.argsort(lens)[-3:], [0]]))
+    cs = np.concatenate([col0[row_ptr[r]:row_ptr[r + 1]].cpu().numpy() for r in rows_s])
+    vs = np.concatenate([val0[row_ptr[r]:row_ptr[r + 1]].cpu().numpy() for r in rows_s])
+    rp_s = np.concatenate([[0], np.cumsum(lens[rows_s])]).astype(np.int32)
+    y_ref, s_ref = oracle.csr_spmv(len(rows_s), rp_s, cs, vs, x.cpu().numpy())
+    err = np.abs(y[torch.from_numpy(rows_s).to(dev)].cpu().numpy() - y_ref)
+    assert np.all(err <= 1e-12 * s_ref + 1e-300)
+    assert bool((y[torch.from_numpy(lens == 0).to(dev)] == 0).all()) and not bool(torch.isnan(y).any())
+    # the CSR baselines at the same size (their entry counters also run up to 2^31 - 1)
+    yb = torch.full((m,), float("nan"), dtype=torch.float64, device=dev)
+    B.csr5_to_csr(h)
+    B.csr5_baseline_csr_vector(m, nnz, row_ptr_d, col, val, x, yb)
+    torch.cuda.synchronize()
+    assert bool(((y - yb).abs() <= 1e-6 * (y.abs() + 1)).all())
+    assert torch.equal(col, col0[:nnz])
+    B.csr5_free(h)
