@@ -85,7 +85,7 @@ size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma);
 /*
  * CSR -> CSR5 (Sections 3.3-3.5; the four steps of Section 5.4).
  *
- *   m, n, nnz   matrix shape, all >= 0, nnz < 2^31.
+ *   m, n, nnz   matrix shape, all >= 0, nnz < 2^31, m <= 2^31 - 2 (else CSR5_ERANGE).
  *   row_ptr     int32[m+1], row_ptr[0] = 0, row_ptr[m] = nnz, non-decreasing.
  *               BORROWED: read now and again by every csr5_spmv (the format
  *               keeps it unchanged, Section 1); must outlive the handle.

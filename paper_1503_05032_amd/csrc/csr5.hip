@@ -176,7 +176,10 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
         // one flag write per wavefront is enough: the lowest lane that sees an empty row
         if (lane_id() == __builtin_ctzll(__ballot(1))) raise_status(status, CSR5_STATUS_HAS_EMPTY_ROWS);
         int t = count_le_tileptr<IT>(tile_ptr, p + 1, uint32_t(r)) - 1;
-        if (t >= 0 && t < p) {
+        // look before the atomic: a tile whose row range holds millions of empty rows
+        // would otherwise receive millions of atomics on one word
+        if (t >= 0 && t < p &&
+            !(__hip_atomic_load(&tile_ptr[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & DIRTY)) {
             tp_t old = __hip_atomic_fetch_or(&tile_ptr[t], DIRTY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (!(old & DIRTY)) raise_status(status, CSR5_STATUS_HAS_DIRTY);
         }
@@ -951,8 +954,10 @@ Layout make_layout(int32_t m, const Geom& g, bool wide) {
 }
 
 // Largest matrix the launches can address: one wavefront per tile and at most
-// 2^32 - 1 threads in a grid; the row-parallel kernels add p_c threads to m.
+// 2^32 - 1 threads in a grid; the row-parallel kernels add p_c threads to m, and
+// all of them form m + 1 in 32 bits.
 bool geometry_fits(int64_t m, int64_t nnz, int sigma) {
+    if (m > int64_t(INT32_MAX) - 1) return false;
     const int64_t T = int64_t(OMEGA) * sigma;
     const int64_t p = (nnz + T - 1) / T;
     return p < (int64_t(1) << 26) - 4 && m + p < (int64_t(1) << 32) - 512;
@@ -985,7 +990,7 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m) {
 size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma) {
     if (m < 0 || nnz < 0) return 0;
     if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
-    if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX) return 0;
+    if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX || !geometry_fits(m, nnz, sigma)) return 0;
     Geom g = make_geom(nnz, sigma);
     return make_layout(m, g, false).total;
 }

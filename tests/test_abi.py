@@ -90,5 +90,8 @@ def test_wide_variant_limits(lib):
     # the conversion refuses such a matrix before touching any pointer (dummy addresses)
     rc, h = B.csr5l_convert_ex(1000, 1000, most + 1, 256, 256, 256, sigma=16, check=False, stream=0)
     assert rc == B.CSR5_ERANGE and not h
+    rc, h = B.csr5_convert_ex(2**31 - 1, 1000, 100, 256, 256, 256, sigma=16, check=False, stream=0)
+    assert rc == B.CSR5_ERANGE and not h          # m + 1 must fit 32 bits
+    assert B.csr5_workspace_bytes(2**31 - 2, 100, 16) > 0
     rc, h = B.csr5l_convert_ex(1000, 1000, 100, 260, 256, 256, sigma=16, check=False, stream=0)
     assert rc == B.CSR5_EINVAL and not h          # int64 row_ptr must be 8-byte aligned

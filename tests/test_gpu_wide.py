@@ -279,3 +279,53 @@ def test_int32_variant_at_its_largest_size():
     assert bool(((y - yb).abs() <= 1e-6 * (y.abs() + 1)).all())
     assert torch.equal(col, col0[:nnz])
     B.csr5_free(h)
+
+
+def test_largest_row_count():
+    """m = 2^31 - 2 rows, nearly all of them empty: the row-parallel conversion
+    kernels and the zero-fill of the fix-up run over 2^31 threads / rows."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60 * 2**30:
+        pytest.skip("needs about 40 GB of GPU memory")
+    dev = torch.device("cuda:0")
+    m, n, sigma = 2**31 - 2, 4096, 4
+    T = 64 * sigma
+    rng = np.random.default_rng(5)
+    live = np.unique(np.concatenate([[0, 1, 5, 1000, 2**20, 2**30 - 1, 2**30, m - 2, m - 1],
+                                     rng.integers(0, m, 60), m - 1 - rng.integers(0, 5000, 20)]))
+    lens_live = rng.integers(1, 300, live.shape[0])
+    lens_live[3] = 5 * T + 7                                   # one row over several tiles
+    nnz = int(lens_live.sum())
+    row_ptr_d = torch.zeros(m + 1, dtype=torch.int32, device=dev)
+    for r, L in zip(live.tolist(), lens_live.tolist()):         # row_ptr[k] = entries in rows < k
+        row_ptr_d[r + 1:] += L
+    say("m", m, "nnz", nnz, "rows with nonzeros", live.shape[0])
+    col_h = np.concatenate([np.sort(rng.choice(n, L, replace=False)) for L in lens_live]).astype(np.int32)
+    val_h = rng.uniform(-1, 1, nnz)
+    x_h = rng.uniform(-1, 1, n)
+    col, val, x = (torch.from_numpy(a).to(dev) for a in (col_h, val_h, x_h))
+    y = torch.full((m,), float("nan"), dtype=torch.float64, device=dev)
+    h = B.csr5_convert_ex(m, n, nnz, row_ptr_d, col, val, sigma=sigma)       # hipMalloc inside, blocking checks
+    st = B.csr5_status(h)
+    assert st & 3 == 0 and st & B.CSR5_STATUS_HAS_EMPTY_ROWS and st & B.CSR5_STATUS_HAS_DIRTY
+    say("converted")
+    row_ptr = row_ptr_d.cpu().numpy()
+    say("row_ptr on the host")
+    ref = oracle.convert(m, n, nnz, row_ptr, col_h, val_h, 64, sigma)
+    say("oracle converted")
+    for which, want in ((B.CSR5_ARRAY_TILE_PTR, ref.tile_ptr), (B.CSR5_ARRAY_TILE_DESC, ref.tile_desc),
+                        (B.CSR5_ARRAY_EMPTY_OFFSET_PTR, ref.empty_offset_ptr),
+                        (B.CSR5_ARRAY_EMPTY_OFFSET, ref.empty_offset)):
+        assert np.array_equal(B.csr5_read_array(h, which), want), which
+    assert np.array_equal(col.cpu().numpy(), ref.col_idx)
+    B.csr5_spmv_ex(h, x, y)
+    torch.cuda.synchronize()
+    say("spmv done")
+    # the rows with nonzeros against Algorithm 1 on a matrix of just those rows; every other row exactly 0
+    rp_s = np.concatenate([[0], np.cumsum(lens_live)]).astype(np.int32)
+    y_ref, s_ref = oracle.csr_spmv(live.shape[0], rp_s, col_h, val_h, x_h)
+    y_live = y[torch.from_numpy(live).to(dev)].cpu().numpy()
+    assert np.all(np.abs(y_live - y_ref) <= 1e-12 * s_ref + 1e-300)
+    assert not bool(torch.isnan(y).any())
+    assert int((y != 0).sum().item()) == int((y_live != 0).sum())
+    B.csr5_free(h)
