@@ -247,6 +247,36 @@ def test_side_stream_and_graph_replay():
     B.csr5_free(h)
 
 
+def test_conversion_in_a_graph():
+    """With a workspace and CSR5_FLAG_NO_HOST_CHECK the conversion only enqueues
+    kernels (no allocation, no memset, no wait), so conversion + SpMV can be
+    captured together; every replay converts the restored CSR arrays again."""
+    a = wl.config(4, scale=0.03)
+    d = DeviceCsr(a)
+    col0, val0 = d.col_idx.clone(), d.val.clone()
+    sigma = 12
+    ws = torch.empty(B.csr5_workspace_bytes(a.m, a.nnz, sigma), dtype=torch.uint8, device="cuda:0")
+    yg = torch.empty_like(d.y)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        d.col_idx.copy_(col0)
+        d.val.copy_(val0)
+        h = B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val, sigma=sigma, workspace=ws,
+                              flags=B.CSR5_FLAG_NO_HOST_CHECK)
+        B.csr5_spmv_ex(h, d.x, yg)
+    y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
+    for k in range(3):
+        ws.fill_(0xAB)                                   # the replay must rebuild everything
+        yg.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.all(np.abs(yg.cpu().numpy()[:a.m] - y_ref) <= 1e-12 * s + 1e-300), ("replay", k)
+        check_format(d, h, ("graph", k))
+    B.csr5_free(h)
+
+
 def test_random_matrices():
     """Randomised parity: mixed row-length distributions (empty runs, short rows,
     a few rows longer than a tile), random shapes and sigma."""
