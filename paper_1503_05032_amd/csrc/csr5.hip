@@ -89,18 +89,6 @@ __device__ __forceinline__ int count_le(const IT* __restrict__ a, int len, int64
     return lo;
 }
 
-// Same over tile_ptr with the empty-row bit masked off.
-template <typename IT>
-__device__ __forceinline__ int count_le_tileptr(const typename Index<IT>::tp_t* a, int len, uint32_t key) {
-    int lo = 0, hi = len;
-    while (lo < hi) {
-        int mid = lo + ((hi - lo) >> 1);
-        auto v = __hip_atomic_load(&a[mid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & Index<IT>::ROWMASK;
-        if (v <= key) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
-
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (OMEGA - 1); }
 
 // Sets a bit of the status word.  Hundreds of thousands of threads may want the
@@ -151,8 +139,12 @@ k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p,
 // Conversion steps 2b + 3a, one thread per matrix row.
 //  * empty row   -> mark the tile whose row range holds it (Algorithm 4, second
 //    loop, turned inside out: the printed loop walks each tile's rows, which
-//    serialises on a tile that spans millions of empty rows; here every empty
-//    row finds its tile by binary search over tile_ptr, same result).
+//    serialises on a tile that spans millions of empty rows).  An empty row
+//    sitting at entry position a lies in the inclusive range
+//    [tile_ptr[t], tile_ptr[t+1]] of exactly one tile, the one that holds entry
+//    a - 1: tiles that start at or after a begin with a later row, tiles that
+//    end before a - 1 end with an earlier one.  Rows before the first nonzero
+//    (a = 0) lie in no tile's range.
 //  * other rows  -> set the bit_flag of the row's first nonzero (Section 3.4;
 //    the scatter of Algorithm 3 step 1) directly inside the packed descriptor.
 // Also validates row_ptr.
@@ -175,7 +167,7 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
     if (a == b) {
         // one flag write per wavefront is enough: the lowest lane that sees an empty row
         if (lane_id() == __builtin_ctzll(__ballot(1))) raise_status(status, CSR5_STATUS_HAS_EMPTY_ROWS);
-        int t = count_le_tileptr<IT>(tile_ptr, p + 1, uint32_t(r)) - 1;
+        const int t = a > 0 ? int((a - 1) / T) : -1;
         // look before the atomic: a tile whose row range holds millions of empty rows
         // would otherwise receive millions of atomics on one word
         if (t >= 0 && t < p &&
@@ -437,7 +429,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
             for (int j = 0; j < SIGMA; j++) buf[lane * PITCH + j] = v[j];
         }
     }
-    __syncthreads();
+    wave_sync_lds();    // every wavefront works in its own LDS slice
     if (active) {
         if (!BACK) {
 #pragma unroll
@@ -452,7 +444,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
 #pragma unroll
         for (int k = 0; k < SIGMA; k++) __builtin_nontemporal_store(v[k], &val[base + k * OMEGA + lane]);
     }
-    __syncthreads();
+    wave_sync_lds();    // every wavefront works in its own LDS slice
     // ---- col_idx, same path through the same LDS buffer
     int32_t c[SIGMA];
     if (active) {
@@ -472,7 +464,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
             for (int j = 0; j < SIGMA; j++) ibuf[lane * PITCH + j] = c[j];
         }
     }
-    __syncthreads();
+    wave_sync_lds();    // every wavefront works in its own LDS slice
     if (active) {
         if (!BACK) {
 #pragma unroll
