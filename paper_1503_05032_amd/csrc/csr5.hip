@@ -195,34 +195,57 @@ template <typename IT>
 __global__ void __launch_bounds__(256)
 k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
             uint32_t* __restrict__ desc, IT* __restrict__ eop) {
-    int tile = blockIdx.x * (blockDim.x / OMEGA) + (threadIdx.x / OMEGA);
-    if (tile >= pc) return;
-    int lane = lane_id();
-    size_t base = size_t(tile) * W * OMEGA + lane;
-    uint64_t flags = desc[base];
-    if (sigma > 32) flags |= uint64_t(desc[base + OMEGA]) << 32;
-    if (lane == 0) flags |= 1u;
-    int cnt = __popcll(flags);
-    int incl = cnt;
+    const int lane = lane_id();
+    const int nwaves = int(gridDim.x) * (blockDim.x / OMEGA);
+    const int first = blockIdx.x * (blockDim.x / OMEGA) + (threadIdx.x / OMEGA);
+    // A tile is 256 bytes of work and one memory round trip: the grid is capped,
+    // every wavefront takes several tiles, and it requests UNROLL of them at once.
+    constexpr int UNROLL = 4;
+    for (int t0 = first; t0 < pc; t0 += UNROLL * nwaves) {
+        uint64_t flags_u[UNROLL];
+        bool dirty_u[UNROLL];
 #pragma unroll
-    for (int d = 1; d < OMEGA; d <<= 1) {
-        int up = __shfl_up(incl, d, OMEGA);
-        if (lane >= d) incl += up;
+        for (int u = 0; u < UNROLL; u++) {
+            const int tile = t0 + u * nwaves;
+            flags_u[u] = 0;
+            dirty_u[u] = false;
+            if (tile < pc) {
+                const size_t base = size_t(tile) * W * OMEGA + lane;
+                flags_u[u] = desc[base];
+                if (sigma > 32) flags_u[u] |= uint64_t(desc[base + OMEGA]) << 32;
+                dirty_u[u] = (tile_ptr[tile] & Index<IT>::DIRTY) != 0;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; u++) {
+            const int tile = t0 + u * nwaves;
+            if (tile >= pc) break;                          // uniform over the wavefront
+            const size_t base = size_t(tile) * W * OMEGA + lane;
+            uint64_t flags = flags_u[u];
+            if (lane == 0) flags |= 1u;
+            int cnt = __popcll(flags);
+            int incl = cnt;
+#pragma unroll
+            for (int d = 1; d < OMEGA; d <<= 1) {
+                int up = __shfl_up(incl, d, OMEGA);
+                if (lane >= d) incl += up;
+            }
+            uint32_t yo = uint32_t(incl - cnt);
+            int total = __shfl(incl, OMEGA - 1, OMEGA);
+            uint64_t heads = __ballot(cnt > 0);
+            uint64_t right = (lane == OMEGA - 1) ? 0ull : (heads >> (lane + 1));
+            uint32_t so = 0;
+            if (cnt > 0) so = right ? uint32_t(__builtin_ctzll(right)) : uint32_t(OMEGA - 1 - lane);
+            // little-endian bit field: flags | seg_offset << sigma | y_offset << (sigma+6)
+            int ysh = sigma + SBITS;  // <= 54
+            uint64_t lo = flags | (uint64_t(so) << sigma) | (uint64_t(yo) << ysh);
+            uint64_t hi = (ysh + ybits > 64) ? (uint64_t(yo) >> (64 - ysh)) : 0ull;
+            desc[base] = uint32_t(lo);
+            if (W > 1) desc[base + OMEGA] = uint32_t(lo >> 32);
+            if (W > 2) desc[base + 2 * OMEGA] = uint32_t(hi);
+            if (lane == 0) eop[tile] = dirty_u[u] ? total : 0;
+        }
     }
-    uint32_t yo = uint32_t(incl - cnt);
-    int total = __shfl(incl, OMEGA - 1, OMEGA);
-    uint64_t heads = __ballot(cnt > 0);
-    uint64_t right = (lane == OMEGA - 1) ? 0ull : (heads >> (lane + 1));
-    uint32_t so = 0;
-    if (cnt > 0) so = right ? uint32_t(__builtin_ctzll(right)) : uint32_t(OMEGA - 1 - lane);
-    // little-endian bit field: flags | seg_offset << sigma | y_offset << (sigma+6)
-    int ysh = sigma + SBITS;  // <= 54
-    uint64_t lo = flags | (uint64_t(so) << sigma) | (uint64_t(yo) << ysh);
-    uint64_t hi = (ysh + ybits > 64) ? (uint64_t(yo) >> (64 - ysh)) : 0ull;
-    desc[base] = uint32_t(lo);
-    if (W > 1) desc[base + OMEGA] = uint32_t(lo >> 32);
-    if (W > 2) desc[base + 2 * OMEGA] = uint32_t(hi);
-    if (lane == 0) eop[tile] = (tile_ptr[tile] & Index<IT>::DIRTY) ? total : 0;
 }
 
 // ----------------------------------------------------------------------------
@@ -1075,7 +1098,9 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         e = hipGetLastError();
     }
     if (e == hipSuccess && g.pc > 0) {   // step 3b
-        hipLaunchKernelGGL(k_tile_desc<IT>, dim3(uint32_t((g.pc + 3) / 4)), dim3(256), 0, s, g.sigma, g.W,
+        uint32_t nb = uint32_t((g.pc + 3) / 4);
+        if (nb > 4096) nb = 4096;                          // 64 wavefronts per CU
+        hipLaunchKernelGGL(k_tile_desc<IT>, dim3(nb), dim3(256), 0, s, g.sigma, g.W,
                            g.ybits, g.pc, tile_ptr, h->tile_desc, eop);
         e = hipGetLastError();
     }
