@@ -277,11 +277,12 @@ def test_conversion_in_a_graph():
     B.csr5_free(h)
 
 
-def test_random_matrices():
+@pytest.mark.parametrize("wide,seed,cases", [(False, 2024, 40), (True, 2025, 30), (False, 7, 60)])
+def test_random_matrices(wide, seed, cases):
     """Randomised parity: mixed row-length distributions (empty runs, short rows,
-    a few rows longer than a tile), random shapes and sigma."""
-    rng = np.random.default_rng(2024)
-    for case in range(40):
+    a few rows longer than a tile), random shapes and sigma; 32- and 64-bit indices."""
+    rng = np.random.default_rng(seed)
+    for case in range(cases):
         sigma = int(rng.integers(1, 49))
         T = 64 * sigma
         m = int(rng.integers(1, 3000))
@@ -298,9 +299,9 @@ def test_random_matrices():
             lens = np.zeros(m, dtype=np.int64)
             idx = rng.integers(0, m, size=max(1, m // 50))
             lens[idx] = rng.integers(1, 2 * T, size=idx.size)
-        a = wl.from_row_lengths(lens, n, seed=case, name=f"random{case}")
+        a = wl.from_row_lengths(lens, n, seed=seed + case, name=f"random{case}")
         say("random", case, "sigma", sigma, a.m, a.n, a.nnz)
-        d = DeviceCsr(a)
+        d = DeviceCsr(a, wide=wide)
         h = convert(d, sigma=sigma, use_workspace=bool(case % 2))
         check_format(d, h, (a.name, sigma))
         check_spmv(d, h, (a.name, sigma))
