@@ -171,11 +171,12 @@ int csr5l_get_arrays(csr5_handle_t h, const uint64_t **tile_ptr, const uint32_t 
                      const int64_t **empty_offset_ptr, const int32_t **empty_offset);
 
 /*
- * Measurement helper: runs the SpMV `reps` times on the stream with HIP events
- * recorded around each of its kernels, waits, and returns the mean duration of
- * each in milliseconds: ms[0] the tile kernel (all complete tiles plus the
- * workgroup for the incomplete one), ms[1] the carry fix-up.  ms is a host
- * array of 2 floats.  y ends up holding A*x as after csr5_spmv.
+ * Measurement helper: launches each of the SpMV's two kernels `reps` times in a
+ * row on the stream, HIP events before and after each series, waits, and returns
+ * the mean duration per launch in milliseconds: ms[0] the tile kernel (all
+ * complete tiles plus the workgroup for the incomplete one), ms[1] the carry
+ * fix-up.  ms is a host array of 2 floats.  A full SpMV follows the two series,
+ * so y ends up holding A*x as after csr5_spmv.
  */
 int csr5_spmv_profile(csr5_handle_t h, const double *x, double *y, void *hip_stream, int reps,
                       float *ms);

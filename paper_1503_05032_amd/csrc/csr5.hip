@@ -9,7 +9,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
-#include <cstdlib>
 #include <new>
 #include <type_traits>
 
@@ -1188,18 +1187,19 @@ int csr5_convert(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int3
 
 }  // extern "C"
 
-// One SpMV: the tile kernel, then the carry fix-up.  `ev`, when given, points at
-// three events recorded before, between and after the two launches.
+// One SpMV: the tile kernel, then the carry fix-up.  `which` selects the launches
+// (measurement only): bit 0 the tile kernel, bit 1 the fix-up.
+constexpr int LAUNCH_TILES = 1, LAUNCH_FIXUP = 2, LAUNCH_BOTH = 3;
+
 template <typename VT, typename IT>
-static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, hipEvent_t* ev) {
+static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, int which) {
     using tp_t = typename Index<IT>::tp_t;
     const IT* row_ptr = static_cast<const IT*>(h->row_ptr);
     const tp_t* tile_ptr = static_cast<const tp_t*>(h->tile_ptr);
     const IT* eop = static_cast<const IT*>(h->eop);
-    if (ev && hipEventRecord(ev[0], s) != hipSuccess) return CSR5_EHIP;
     hipError_t e = hipSuccess;
     VT* carry = static_cast<VT*>(h->carry);
-    if (h->nnz > 0) {
+    if (h->nnz > 0 && (which & LAUNCH_TILES)) {
         switch (h->g.sigma) {
 #define X(S) case S: e = launch_spmv<S, VT, IT>(h->g, h->m, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, eop, \
                                                 h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y,    \
@@ -1210,8 +1210,7 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, hi
         }
     }
     if (e != hipSuccess) return CSR5_EHIP;
-    if (ev && hipEventRecord(ev[1], s) != hipSuccess) return CSR5_EHIP;
-    {
+    if (which & LAUNCH_FIXUP) {
         // one thread per tile; when the matrix has empty rows the same grid strides over the rows
         int ntiles = h->g.p;
         size_t nb = (size_t(ntiles) + 255) / 256;
@@ -1223,18 +1222,17 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, hi
                            tile_ptr, carry, y, h->status);
         if (hipGetLastError() != hipSuccess) return CSR5_EHIP;
     }
-    if (ev && hipEventRecord(ev[2], s) != hipSuccess) return CSR5_EHIP;
     return CSR5_OK;
 }
 
 // The 64-bit index variant exists for double only.
 template <typename VT>
-static int spmv_launch(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, hipEvent_t* ev) {
+static int spmv_launch(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, int which = LAUNCH_BOTH) {
     if constexpr (std::is_same<VT, double>::value) {
-        if (h->wide) return spmv_launch_it<double, int64_t>(h, x, y, s, ev);
+        if (h->wide) return spmv_launch_it<double, int64_t>(h, x, y, s, which);
     }
     if (h->wide) return CSR5_EINVAL;
-    return spmv_launch_it<VT, int32_t>(h, x, y, s, ev);
+    return spmv_launch_it<VT, int32_t>(h, x, y, s, which);
 }
 
 template <typename VT>
@@ -1244,7 +1242,7 @@ static int spmv_checked(csr5_handle_t h, const VT* x, VT* y, void* hip_stream) {
     if (h->m > 0 && !y) return CSR5_EINVAL;
     if (h->nnz > 0 && !x) return CSR5_EINVAL;
     if (h->m == 0) return CSR5_OK;
-    return spmv_launch<VT>(h, x, y, static_cast<hipStream_t>(hip_stream), nullptr);
+    return spmv_launch<VT>(h, x, y, static_cast<hipStream_t>(hip_stream));
 }
 
 template <typename VT>
@@ -1253,31 +1251,30 @@ static int spmv_profile(csr5_handle_t h, const VT* x, VT* y, void* hip_stream, i
     if (!h || !h->in_csr5_order || h->dtype != want || !ms || reps <= 0 || reps > 100000) return CSR5_EINVAL;
     if (h->m == 0 || !y || (h->nnz > 0 && !x)) return CSR5_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    size_t nev = size_t(reps) * 3;
-    hipEvent_t* ev = static_cast<hipEvent_t*>(std::calloc(nev, sizeof(hipEvent_t)));
-    if (!ev) return CSR5_ENOMEM;
+    // Each kernel is launched `reps` times in a row between two events: consecutive
+    // launches hide each other's dispatch latency, so elapsed / reps is the kernel's
+    // duration (an event pair around a single launch would add that latency).
+    // What the repeated launches leave in y is overwritten by the full SpMV at the end.
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     int rc = CSR5_OK;
-    size_t made = 0;
-    for (; made < nev; made++)
-        if (hipEventCreate(&ev[made]) != hipSuccess) { rc = CSR5_EHIP; break; }
-    for (int r = 0; rc == CSR5_OK && r < reps; r++) rc = spmv_launch<VT>(h, x, y, s, ev + size_t(r) * 3);
+    for (int k = 0; k < 3 && rc == CSR5_OK; k++)
+        if (hipEventCreate(&ev[k]) != hipSuccess) rc = CSR5_EHIP;
+    if (rc == CSR5_OK && hipEventRecord(ev[0], s) != hipSuccess) rc = CSR5_EHIP;
+    for (int r = 0; rc == CSR5_OK && r < reps; r++) rc = spmv_launch<VT>(h, x, y, s, LAUNCH_TILES);
+    if (rc == CSR5_OK && hipEventRecord(ev[1], s) != hipSuccess) rc = CSR5_EHIP;
+    for (int r = 0; rc == CSR5_OK && r < reps; r++) rc = spmv_launch<VT>(h, x, y, s, LAUNCH_FIXUP);
+    if (rc == CSR5_OK && hipEventRecord(ev[2], s) != hipSuccess) rc = CSR5_EHIP;
+    if (rc == CSR5_OK) rc = spmv_launch<VT>(h, x, y, s);
     if (hipStreamSynchronize(s) != hipSuccess && rc == CSR5_OK) rc = CSR5_EHIP;
-    double acc[2] = {0.0, 0.0};
-    for (int r = 0; rc == CSR5_OK && r < reps; r++) {
-        float a = 0.f, b = 0.f;
-        if (hipEventElapsedTime(&a, ev[size_t(r) * 3], ev[size_t(r) * 3 + 1]) != hipSuccess ||
-            hipEventElapsedTime(&b, ev[size_t(r) * 3 + 1], ev[size_t(r) * 3 + 2]) != hipSuccess) {
-            rc = CSR5_EHIP;
-            break;
-        }
-        acc[0] += a;
-        acc[1] += b;
-    }
-    for (size_t k = 0; k < made; k++) (void)hipEventDestroy(ev[k]);
-    std::free(ev);
+    float a = 0.f, b = 0.f;
+    if (rc == CSR5_OK && (hipEventElapsedTime(&a, ev[0], ev[1]) != hipSuccess ||
+                          hipEventElapsedTime(&b, ev[1], ev[2]) != hipSuccess))
+        rc = CSR5_EHIP;
+    for (int k = 0; k < 3; k++)
+        if (ev[k]) (void)hipEventDestroy(ev[k]);
     if (rc == CSR5_OK) {
-        ms[0] = float(acc[0] / reps);   // tile kernel
-        ms[1] = float(acc[1] / reps);   // carry fix-up
+        ms[0] = a / float(reps);   // tile kernel
+        ms[1] = b / float(reps);   // carry fix-up
     }
     return rc;
 }

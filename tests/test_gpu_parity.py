@@ -363,3 +363,18 @@ def test_single_precision_full_size(cfg):
     a = wl.config(cfg)
     say("f32", a.stats())
     _run32(a, 0)
+
+
+def test_profile_helper_leaves_y_correct():
+    """csr5_spmv_profile launches each kernel many times in a row and then runs one
+    full SpMV: durations are positive and y is A*x afterwards."""
+    a = wl.config(4, scale=0.02)
+    d = DeviceCsr(a)
+    h = convert(d, sigma=0)
+    d.y.fill_(float("nan"))
+    ms_tiles, ms_fixup = B.csr5_spmv_profile(h, d.x, d.y, reps=20)
+    torch.cuda.synchronize()
+    assert 0 < ms_tiles < 10 and 0 < ms_fixup < 10
+    y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
+    assert np.all(np.abs(d.y.cpu().numpy()[:a.m] - y_ref) <= 1e-12 * s + 1e-300)
+    B.csr5_free(h)
