@@ -10,7 +10,8 @@
  * entry points; csr5s_ is the single-precision and csr5l_ the 64-bit-index
  * variant of the conversion, and their handles go through the same calls.  A
  * handle is tied to the device that was current when it was made: call with that
- * device current and with pointers to its memory.  The tile
+ * device current (csr5_spmv* return CSR5_EINVAL otherwise) and with pointers to
+ * its memory.  The tile
  * width omega is fixed to 64, the wavefront width (Section 3.2); sigma, the tile
  * height, is chosen per matrix.  T = omega*sigma nonzeros per tile,
  * p = ceil(nnz/T) tiles, p_c = floor(nnz/T) complete tiles (Section 3.1, 3.3).

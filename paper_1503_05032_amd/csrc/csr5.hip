@@ -938,6 +938,7 @@ struct csr5_handle_s {
     void* carry;           // one 8-byte slot per tile (incomplete one included): cross-tile sums of an SpMV
     void* owned;           // hipMalloc'ed block, or NULL when a workspace was given
     hipStream_t conv_stream;
+    int device;            // HIP device that was current at conversion
     bool in_csr5_order;
 };
 
@@ -1078,6 +1079,11 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     h->carry = basep + L.off_carry;
     h->status = reinterpret_cast<uint32_t*>(basep + L.off_status);
     h->conv_stream = s;
+    if (hipGetDevice(&h->device) != hipSuccess) {
+        if (h->owned) (void)hipFree(h->owned);
+        delete h;
+        return CSR5_EHIP;
+    }
     h->in_csr5_order = true;
     tp_t* const tile_ptr = static_cast<tp_t*>(h->tile_ptr);
     IT* const eop = static_cast<IT*>(h->eop);
@@ -1239,6 +1245,9 @@ template <typename VT>
 static int spmv_checked(csr5_handle_t h, const VT* x, VT* y, void* hip_stream) {
     constexpr int want = std::is_same<VT, float>::value ? CSR5_DTYPE_F32 : CSR5_DTYPE_F64;
     if (!h || !h->in_csr5_order || h->dtype != want) return CSR5_EINVAL;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return CSR5_EHIP;
+    if (dev != h->device) return CSR5_EINVAL;              // the handle's arrays live on another device
     if (h->m > 0 && !y) return CSR5_EINVAL;
     if (h->nnz > 0 && !x) return CSR5_EINVAL;
     if (h->m == 0) return CSR5_OK;
