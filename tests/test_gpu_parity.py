@@ -378,3 +378,31 @@ def test_profile_helper_leaves_y_correct():
     y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)
     assert np.all(np.abs(d.y.cpu().numpy()[:a.m] - y_ref) <= 1e-12 * s + 1e-300)
     B.csr5_free(h)
+
+
+@pytest.mark.parametrize("sigma", [4, 16, 40])
+def test_non_finite_x_stays_in_its_rows(sigma):
+    """An infinite or NaN entry of x must reach exactly the rows that reference its
+    column: segment sums are formed directly, not as differences of tile-wide
+    prefix sums (the hazard of taking Algorithm 6 literally)."""
+    a = wl.from_row_lengths(np.random.default_rng(sigma).integers(0, 40, size=1500), 600, seed=sigma, name="nonfinite")
+    x = a.x.copy()
+    x[7] = np.inf
+    x[300] = -np.inf
+    x[451] = np.nan
+    d = DeviceCsr(a)
+    h = convert(d, sigma=sigma)
+    d.x = torch.from_numpy(x).to("cuda:0")
+    d.y.fill_(0.0)
+    B.csr5_spmv_ex(h, d.x, d.y)
+    torch.cuda.synchronize()
+    y = d.y.cpu().numpy()[:a.m]
+    with np.errstate(invalid="ignore", over="ignore"):
+        y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, x)
+    fin = np.isfinite(y_ref)
+    assert 50 < (~fin).sum() < a.m - 50                       # both kinds of rows are present
+    assert np.all(np.isfinite(y[fin])) and np.all(np.abs(y[fin] - y_ref[fin]) <= 1e-12 * s[fin] + 1e-300)
+    assert np.array_equal(np.isnan(y[~fin]), np.isnan(y_ref[~fin]))
+    inf_rows = ~fin & ~np.isnan(y_ref)
+    assert np.array_equal(y[inf_rows], y_ref[inf_rows])        # same signed infinity
+    B.csr5_free(h)
