@@ -103,14 +103,37 @@ __device__ __forceinline__ void atomic_add_fp(VT* addr, VT v) {
     __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Workgroups are dealt round-robin to the 8 XCDs.  Give every XCD one
-// contiguous range of logical blocks instead, so that neighbouring tiles (which
-// gather neighbouring parts of x) share one L2 rather than eight.
-__device__ __forceinline__ uint32_t xcd_remap(uint32_t w, uint32_t nb) {
-    uint32_t per = nb / NUM_XCD, rem = nb % NUM_XCD;
-    uint32_t xcd = w % NUM_XCD, k = w / NUM_XCD;
-    uint32_t start = xcd * per + (xcd < rem ? xcd : rem);
-    return start + k;
+// Which tiles a workgroup takes.  Workgroups are dealt round-robin to the 8
+// XCDs (workgroup w runs on XCD w mod 8), each with its own L2.  Three orders,
+// chosen per matrix at launch (measured on stencil, power-law and banded random
+// matrices from 3 M to 2.2 G nonzeros; the crossovers sat at the same places in
+// all families):
+//  * contiguous (chunk = 0): XCD k gets the k-th eighth of the tiles, so
+//    neighbouring tiles, which gather neighbouring parts of x, share one L2.
+//    Wins by 1-14 % while x is at most about 9 MiB, i.e. while the part of x one
+//    XCD works on stays in its L2 next to the streamed tiles; beyond that it
+//    loses 2-9 %: eight distant streams cost more than a shared sweep.
+//  * plain (chunk = 1): workgroup w takes tiles 4w..4w+3; all XCDs sweep the same
+//    region, and expensive stretches (a long row's tiles) are spread evenly.
+//    But neighbouring tiles then sit on different XCDs, and when a tile holds
+//    fewer rows than a cache line of y (16), every line of y is written piecewise
+//    from several L2s: 8 % slower on a matrix with 350 nonzeros per row.
+//  * chunked (chunk = 16): runs of 16 workgroups go to the XCDs in turn; as good
+//    as plain on regular matrices and without its piecewise writes.
+constexpr size_t XCD_CONTIGUOUS_MAX_X_BYTES = 10u * 1000u * 1000u;
+constexpr uint32_t XCD_CHUNK = 16;
+constexpr int Y_LINE_ROWS = 16;            // 128-byte line / 8-byte value
+
+__device__ __forceinline__ uint32_t xcd_order(uint32_t w, uint32_t nb, uint32_t chunk) {
+    const uint32_t xcd = w % NUM_XCD, k = w / NUM_XCD;
+    if (chunk == 0) {
+        const uint32_t per = nb / NUM_XCD, rem = nb % NUM_XCD;
+        return xcd * per + (xcd < rem ? xcd : rem) + k;
+    }
+    // a permutation of [0, full); the ragged rest keeps the plain order
+    const uint32_t full = (nb / (NUM_XCD * chunk)) * (NUM_XCD * chunk);
+    if (w >= full) return w;
+    return (k / chunk) * (NUM_XCD * chunk) + xcd * chunk + (k % chunk);
 }
 
 // ----------------------------------------------------------------------------
@@ -616,7 +639,7 @@ __device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
 
 template <int SIGMA, typename VT, typename IT>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
-k_spmv(int m, IT nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
+k_spmv(int m, IT nnz, int pc, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd_chunk,
        const IT* __restrict__ row_ptr, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
        const uint32_t* __restrict__ tile_desc, const IT* __restrict__ eop,
        const int32_t* __restrict__ eo, const int32_t* __restrict__ col_idx,
@@ -643,7 +666,7 @@ k_spmv(int m, IT nnz, int pc, uint32_t nb_tiles, uint32_t has_tail,
     }
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / OMEGA);
-    const int tile = int(xcd_remap(blockIdx.x - has_tail, nb_tiles)) * WAVES + wave;
+    const int tile = int(xcd_order(blockIdx.x - has_tail, nb_tiles, xcd_chunk)) * WAVES + wave;
     if (tile >= pc) return;
 
     // ---- stream the tile.  val: at step j the 64 lanes read 64 consecutive
@@ -849,7 +872,7 @@ k_spmv_fixup(int m, int ntiles, const IT* __restrict__ row_ptr,
 }
 
 template <int SIGMA, typename VT, typename IT>
-hipError_t launch_spmv(const Geom& g, int m, IT nnz, const IT* row_ptr,
+hipError_t launch_spmv(const Geom& g, int m, int n, IT nnz, const IT* row_ptr,
                        const typename Index<IT>::tp_t* tile_ptr,
                        const uint32_t* tile_desc, const IT* eop, const int32_t* eo,
                        const int32_t* col_idx, const VT* val, const VT* x, VT* y,
@@ -859,8 +882,11 @@ hipError_t launch_spmv(const Geom& g, int m, IT nnz, const IT* row_ptr,
     uint32_t has_tail = (int64_t(g.pc) * g.T < nnz) ? 1u : 0u;
     uint32_t nb = nb_tiles + has_tail;
     if (nb == 0) return hipSuccess;
+    uint32_t xcd_chunk = 0;                                        // contiguous eighths
+    if (size_t(n) * sizeof(VT) > XCD_CONTIGUOUS_MAX_X_BYTES)       // x too large for that to pay
+        xcd_chunk = (int64_t(nnz) / (m > 0 ? m : 1) <= g.T / Y_LINE_ROWS) ? 1u : XCD_CHUNK;
     hipLaunchKernelGGL((k_spmv<SIGMA, VT, IT>), dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, nb_tiles, has_tail,
-                       row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status);
+                       xcd_chunk, row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status);
     return hipGetLastError();
 }
 
@@ -1207,7 +1233,7 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, in
     VT* carry = static_cast<VT*>(h->carry);
     if (h->nnz > 0 && (which & LAUNCH_TILES)) {
         switch (h->g.sigma) {
-#define X(S) case S: e = launch_spmv<S, VT, IT>(h->g, h->m, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, eop, \
+#define X(S) case S: e = launch_spmv<S, VT, IT>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, eop, \
                                                 h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y,    \
                                                 carry, h->status, s); break;
             CSR5_FOR_SIGMA(X)
