@@ -335,8 +335,8 @@ def main():
 # keyed by (workload, sigma).  profiles/k_spmv_hbm_traffic_pmc.md and
 # profiles/k_spmv_huge_mixed_kernel_trace_and_traffic.md have the runs.
 MEASURED_TRAFFIC: dict = {
-    (2, 16): int((2.000 * 164521.5 + 8014.8) * 1024),     # stencil: 336.9 MB read + 8.2 MB written
-    (3, 16): int((2.000 * 183718.9 + 15965.8) * 1024),    # power-law: 376.3 MB read + 16.3 MB written
+    (2, 16): int((2.000 * 164523.1 + 8014.9) * 1024),     # stencil: 336.9 MB read + 8.2 MB written
+    (3, 16): int((2.000 * 176192.6 + 15956.8) * 1024),    # power-law: 360.8 MB read + 16.3 MB written
     (7, 16): int((2.000 * 13661631.8 + 67157.0) * 1024),  # huge_mixed: 27.98 GB read + 68.8 MB written
 }
 
