@@ -19,6 +19,11 @@ namespace {
 constexpr int OMEGA = CSR5_OMEGA;
 constexpr int SBITS = 6;  // ceil(log2 omega)
 constexpr uint32_t BAD_BITS = CSR5_STATUS_BAD_ROW_PTR | CSR5_STATUS_BAD_COL_IDX;
+// Internal status bit (not reported): some COMPLETE tile is marked, so the
+// empty_offset layout has to be scanned.  Set by k_tile_desc only; the scan
+// kernels decide on it, and nothing in their own launches changes it.
+constexpr uint32_t STATUS_SCAN_NEEDED = 1u << 16;
+constexpr uint32_t STATUS_PUBLIC = 0xffu;
 constexpr int NUM_XCD = 8;  // MI355X: 8 accelerator dies, each with its own L2
 
 // sigma rule constants <r, s, t, u> for MI355X (Section 3.2 leaves them to the
@@ -94,7 +99,7 @@ __device__ __forceinline__ int lane_id() { return threadIdx.x & (OMEGA - 1); }
 // same bit, and atomics on one address are served one after the other, so look
 // first: after the first few, everybody finds it set.
 __device__ __forceinline__ void raise_status(uint32_t* status, uint32_t bit) {
-    if (!(__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(status, bit);
+    if ((__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit) != bit) atomicOr(status, bit);
 }
 
 // Native global floating-point atomic add (fp64 or fp32), no return value.
@@ -177,33 +182,51 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
        typename Index<IT>::tp_t* tile_ptr, uint32_t* desc, uint32_t* status) {
     using tp_t = typename Index<IT>::tp_t;
     constexpr tp_t DIRTY = Index<IT>::DIRTY;
+    const int lane = lane_id();
     const int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (g >= int64_t(m)) return;
-    const int r = int(g);
-    IT a = row_ptr[r], b = row_ptr[r + 1];
-    bool bad = (a < 0) || (b < a) || (b > nnz) || (r == 0 && a != 0) || (r == m - 1 && b != nnz);
-    if (bad) {
-        raise_status(status, CSR5_STATUS_BAD_ROW_PTR);
-        return;
+    const bool in = g < int64_t(m);                       // every lane stays for the shuffles below
+    const int r = in ? int(g) : 0;
+    IT a = 0, b = 0;
+    if (in) { a = row_ptr[r]; b = row_ptr[r + 1]; }
+    const bool bad = in && ((a < 0) || (b < a) || (b > nnz) || (r == 0 && a != 0) || (r == m - 1 && b != nnz));
+    if (bad) raise_status(status, CSR5_STATUS_BAD_ROW_PTR);
+    // Empty row: mark its tile.  Neighbouring empty rows aim at the same tile, so
+    // only the first lane of such a run goes on, and it looks before the atomic (a
+    // tile whose range holds millions of empty rows would otherwise receive
+    // millions of atomics on one word).  The status bits that say "some tile is
+    // marked" are set once, by the scan that follows; only rows before the first
+    // nonzero mark no tile, and row 0 speaks for them.
+    const bool empty = in && !bad && a == b;
+    if (empty && r == 0) raise_status(status, CSR5_STATUS_HAS_EMPTY_ROWS);
+    const int t = (empty && a > 0) ? int((a - 1) / T) : -1 - lane;
+    const int tprev = __shfl_up(t, 1, OMEGA);
+    if (t >= 0 && t < p && (lane == 0 || tprev != t) &&
+        !(__hip_atomic_load(&tile_ptr[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & DIRTY))
+        __hip_atomic_fetch_or(&tile_ptr[t], DIRTY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // The flag of the row's first nonzero.  Short rows put the flags of several
+    // consecutive rows, i.e. lanes, into one descriptor word, and atomics on one
+    // word are served one after the other (2 M rows of a power-law matrix: 75 us).
+    // So the lanes that aim at the same word merge their bits first (the rows are
+    // in order, hence those lanes are neighbours) and the last of them issues one OR.
+    const bool sets = in && !bad && a != b && int64_t(a) < int64_t(pc) * T;
+    uint64_t word = ~uint64_t(lane);                      // no real word index, different in every lane
+    uint32_t bits = 0;
+    if (sets) {
+        const int tile = int(a / T);
+        const int w = int(a - IT(tile) * T);
+        const int i = w / sigma;
+        const int j = w - i * sigma;
+        word = (uint64_t(tile) * W + (j >> 5)) * OMEGA + i;
+        bits = 1u << (j & 31);
     }
-    if (a == b) {
-        // one flag write per wavefront is enough: the lowest lane that sees an empty row
-        if (lane_id() == __builtin_ctzll(__ballot(1))) raise_status(status, CSR5_STATUS_HAS_EMPTY_ROWS);
-        const int t = a > 0 ? int((a - 1) / T) : -1;
-        // look before the atomic: a tile whose row range holds millions of empty rows
-        // would otherwise receive millions of atomics on one word
-        if (t >= 0 && t < p &&
-            !(__hip_atomic_load(&tile_ptr[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & DIRTY)) {
-            tp_t old = __hip_atomic_fetch_or(&tile_ptr[t], DIRTY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (!(old & DIRTY)) raise_status(status, CSR5_STATUS_HAS_DIRTY);
-        }
-    } else if (int64_t(a) < int64_t(pc) * T) {
-        int tile = int(a / T);
-        int w = int(a - IT(tile) * T);
-        int i = w / sigma;
-        int j = w - i * sigma;
-        atomicOr(&desc[(size_t(tile) * W + (j >> 5)) * OMEGA + i], 1u << (j & 31));
+#pragma unroll
+    for (int d = 1; d < OMEGA; d <<= 1) {
+        const uint32_t up = __shfl_up(bits, d, OMEGA);
+        const uint64_t wup = __shfl_up(word, d, OMEGA);
+        if (lane >= d && wup == word) bits |= up;
     }
+    const uint64_t wnext = __shfl_down(word, 1, OMEGA);
+    if (sets && (lane == OMEGA - 1 || wnext != word)) atomicOr(&desc[word], bits);
 }
 
 // ----------------------------------------------------------------------------
@@ -216,13 +239,14 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
 template <typename IT>
 __global__ void __launch_bounds__(256)
 k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
-            uint32_t* __restrict__ desc, IT* __restrict__ eop) {
+            uint32_t* __restrict__ desc, IT* __restrict__ eop, uint32_t* __restrict__ status) {
     const int lane = lane_id();
     const int nwaves = int(gridDim.x) * (blockDim.x / OMEGA);
     const int first = blockIdx.x * (blockDim.x / OMEGA) + (threadIdx.x / OMEGA);
     // A tile is 256 bytes of work and one memory round trip: the grid is capped,
     // every wavefront takes several tiles, and it requests UNROLL of them at once.
     constexpr int UNROLL = 4;
+    bool met_marked = false;
     for (int t0 = first; t0 < pc; t0 += UNROLL * nwaves) {
         uint64_t flags_u[UNROLL];
         bool dirty_u[UNROLL];
@@ -266,20 +290,30 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
             if (W > 1) desc[base + OMEGA] = uint32_t(lo >> 32);
             if (W > 2) desc[base + 2 * OMEGA] = uint32_t(hi);
             if (lane == 0) eop[tile] = dirty_u[u] ? total : 0;
+            met_marked |= dirty_u[u];
         }
     }
+    // "some tile is marked" (and hence "some row is empty"): once per workgroup, not
+    // once per empty row -- everything that aims at the one status word queues up
+    __shared__ int wg_met_marked;
+    if (threadIdx.x == 0) wg_met_marked = 0;
+    __syncthreads();
+    if (met_marked && lane == 0) wg_met_marked = 1;
+    __syncthreads();
+    if (threadIdx.x == 0 && wg_met_marked)
+        raise_status(status, CSR5_STATUS_HAS_DIRTY | CSR5_STATUS_HAS_EMPTY_ROWS | STATUS_SCAN_NEEDED);
 }
 
 // ----------------------------------------------------------------------------
 // empty_offset layout: exclusive prefix sum of the per-tile segment counts
 // (non-zero only for tiles with an empty row); the array has p_c + 1 entries.
-// Nothing to scan when no tile is marked.  Up to SCAN_SINGLE tiles one workgroup
-// walks the array chunk by chunk; beyond that every chunk gets a workgroup
-// (local scan + chunk total), one workgroup scans the chunk totals, and a third
-// launch adds them back.
+// Nothing to scan when no tile is marked (status bit from k_tile_desc).  Up to
+// SCAN_SINGLE tiles one workgroup walks the array chunk by chunk; beyond that
+// every chunk gets a workgroup (local scan + chunk total) and a second launch
+// adds to every chunk the sum of the totals before it.
 // ----------------------------------------------------------------------------
 constexpr int SCAN_THREADS = 1024, SCAN_ITEMS = 8, SCAN_CHUNK = SCAN_THREADS * SCAN_ITEMS;
-constexpr int SCAN_SINGLE = 8 * SCAN_CHUNK;
+constexpr int SCAN_SINGLE = 4 * SCAN_CHUNK;
 
 // Exclusive scan of a[base .. base + SCAN_CHUNK) (entries at or beyond len count
 // as 0) by one workgroup of SCAN_THREADS threads, in place, plus `carry`;
@@ -327,47 +361,71 @@ __device__ IT scan_chunk(IT* __restrict__ a, int64_t base, int64_t len, IT carry
     return total;
 }
 
+// The last words of the scan: the total number of entries, and the status bits
+// for a marked incomplete tile (it has no descriptor, so k_tile_desc never sees
+// it).  One thread.
 template <typename IT>
-__global__ void __launch_bounds__(SCAN_THREADS)
-k_scan_eop(int pc, IT* __restrict__ eop, const uint32_t* __restrict__ status) {
-    if (!(*status & CSR5_STATUS_HAS_DIRTY)) {
-        if (threadIdx.x == 0) eop[pc] = 0;
-        return;
-    }
-    IT carry = 0;
-    for (int64_t base = 0; base < pc; base += SCAN_CHUNK) carry += scan_chunk(eop, base, int64_t(pc), carry);
-    if (threadIdx.x == 0) eop[pc] = carry;
+__device__ __forceinline__ void scan_epilogue(int pc, int p, IT total, IT* __restrict__ eop,
+                                              const typename Index<IT>::tp_t* __restrict__ tile_ptr,
+                                              uint32_t* __restrict__ status) {
+    eop[pc] = total;
+    if (p > pc && (tile_ptr[pc] & Index<IT>::DIRTY))
+        atomicOr(status, CSR5_STATUS_HAS_DIRTY | CSR5_STATUS_HAS_EMPTY_ROWS);
 }
 
-// large arrays, step 1: workgroup b scans chunk b on its own
+template <typename IT>
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_scan_eop(int pc, int p, IT* __restrict__ eop, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
+           uint32_t* __restrict__ status) {
+    IT total = 0;
+    if (*status & STATUS_SCAN_NEEDED)
+        for (int64_t base = 0; base < pc; base += SCAN_CHUNK) total += scan_chunk(eop, base, int64_t(pc), total);
+    if (threadIdx.x == 0) scan_epilogue(pc, p, total, eop, tile_ptr, status);
+}
+
+// more than SCAN_SINGLE tiles, step 1: workgroup b scans chunk b on its own
 template <typename IT>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_chunks(int pc, IT* __restrict__ eop, IT* __restrict__ chunk_sum, const uint32_t* __restrict__ status) {
-    if (!(*status & CSR5_STATUS_HAS_DIRTY)) return;
-    IT total = scan_chunk(eop, int64_t(blockIdx.x) * SCAN_CHUNK, int64_t(pc), IT(0));
+    if (!(*status & STATUS_SCAN_NEEDED)) return;
+    const IT total = scan_chunk(eop, int64_t(blockIdx.x) * SCAN_CHUNK, int64_t(pc), IT(0));
     if (threadIdx.x == 0) chunk_sum[blockIdx.x] = total;
 }
 
-// step 2: one workgroup scans the chunk totals (at most SCAN_CHUNK of them)
+// step 2: workgroup b sums the totals of the chunks before its own (at most
+// SCAN_CHUNK of them) and adds that to its chunk; the last one finishes the array
 template <typename IT>
 __global__ void __launch_bounds__(SCAN_THREADS)
-k_scan_chunk_sums(int pc, int nchunks, IT* __restrict__ eop, IT* __restrict__ chunk_sum,
-                  const uint32_t* __restrict__ status) {
-    if (!(*status & CSR5_STATUS_HAS_DIRTY)) {
-        if (threadIdx.x == 0) eop[pc] = 0;
+k_scan_finish(int pc, int p, IT* __restrict__ eop, const IT* __restrict__ chunk_sum,
+              const typename Index<IT>::tp_t* __restrict__ tile_ptr, uint32_t* __restrict__ status) {
+    const int b = blockIdx.x, last = int(gridDim.x) - 1;
+    if (!(*status & STATUS_SCAN_NEEDED)) {
+        if (b == last && threadIdx.x == 0) scan_epilogue(pc, p, IT(0), eop, tile_ptr, status);
         return;
     }
-    IT total = scan_chunk(chunk_sum, 0, int64_t(nchunks), IT(0));
-    if (threadIdx.x == 0) eop[pc] = total;
-}
-
-// step 3: add every chunk's offset
-template <typename IT>
-__global__ void __launch_bounds__(256)
-k_scan_add(int pc, IT* __restrict__ eop, const IT* __restrict__ chunk_sum, const uint32_t* __restrict__ status) {
-    if (!(*status & CSR5_STATUS_HAS_DIRTY)) return;
-    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i < pc) eop[i] += chunk_sum[i / SCAN_CHUNK];
+    __shared__ IT wave_part[SCAN_THREADS / OMEGA];
+    __shared__ IT before;
+    const int lane = lane_id(), wave = threadIdx.x / OMEGA;
+    IT part = 0;
+    for (int c = threadIdx.x; c < b; c += SCAN_THREADS) part += chunk_sum[c];
+#pragma unroll
+    for (int d = OMEGA / 2; d >= 1; d >>= 1) part += __shfl_down(part, d, OMEGA);
+    if (lane == 0) wave_part[wave] = part;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        IT sum = 0;
+        for (int k = 0; k < SCAN_THREADS / OMEGA; k++) sum += wave_part[k];
+        before = sum;
+    }
+    __syncthreads();
+    const IT offset = before;
+    if (offset != 0) {
+        const int64_t i0 = int64_t(b) * SCAN_CHUNK + int64_t(threadIdx.x) * SCAN_ITEMS;
+#pragma unroll
+        for (int q = 0; q < SCAN_ITEMS; q++)
+            if (i0 + q < pc) eop[i0 + q] += offset;
+    }
+    if (b == last && threadIdx.x == 0) scan_epilogue(pc, p, IT(offset + chunk_sum[b]), eop, tile_ptr, status);
 }
 
 // ----------------------------------------------------------------------------
@@ -1132,20 +1190,18 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         uint32_t nb = uint32_t((g.pc + 3) / 4);
         if (nb > 4096) nb = 4096;                          // 64 wavefronts per CU
         hipLaunchKernelGGL(k_tile_desc<IT>, dim3(nb), dim3(256), 0, s, g.sigma, g.W,
-                           g.ybits, g.pc, tile_ptr, h->tile_desc, eop);
+                           g.ybits, g.pc, tile_ptr, h->tile_desc, eop, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && g.pc <= SCAN_SINGLE) {
-        hipLaunchKernelGGL(k_scan_eop<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, eop, h->status);
+        hipLaunchKernelGGL(k_scan_eop<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, tile_ptr, h->status);
         e = hipGetLastError();
     } else if (e == hipSuccess) {
         IT* chunk_sum = reinterpret_cast<IT*>(basep + L.off_scan);
-        const int nchunks = (g.pc + SCAN_CHUNK - 1) / SCAN_CHUNK;      // <= 2^26 / 2^13
+        const int nchunks = (g.pc + SCAN_CHUNK - 1) / SCAN_CHUNK;      // <= 2^26 / 2^13 = SCAN_CHUNK
         hipLaunchKernelGGL(k_scan_chunks<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, eop, chunk_sum, h->status);
-        hipLaunchKernelGGL(k_scan_chunk_sums<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, nchunks, eop, chunk_sum,
-                           h->status);
-        hipLaunchKernelGGL(k_scan_add<IT>, dim3(uint32_t((size_t(g.pc) + 255) / 256)), dim3(256), 0, s, g.pc, eop,
-                           chunk_sum, h->status);
+        hipLaunchKernelGGL(k_scan_finish<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, chunk_sum,
+                           tile_ptr, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && g.pc > 0 && m > 0) {
@@ -1363,6 +1419,7 @@ int csr5_status(csr5_handle_t h, uint32_t* status) {
     if (!h || !status) return CSR5_EINVAL;
     if (hipMemcpyAsync(status, h->status, 4, hipMemcpyDeviceToHost, h->conv_stream) != hipSuccess) return CSR5_EHIP;
     if (hipStreamSynchronize(h->conv_stream) != hipSuccess) return CSR5_EHIP;
+    *status &= STATUS_PUBLIC;
     return CSR5_OK;
 }
 
