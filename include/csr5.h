@@ -53,7 +53,7 @@ enum {
 
 /* csr5_convert_ex flags */
 #define CSR5_FLAG_NONE 0u
-#define CSR5_FLAG_NO_HOST_CHECK 1u /* skip the blocking read of row_ptr[0], row_ptr[m] */
+#define CSR5_FLAG_NO_HOST_CHECK 1u /* do not wait for the device-side checks of the input: only enqueue */
 
 /* bits of the device-side status word reported by csr5_status */
 #define CSR5_STATUS_BAD_ROW_PTR 1u /* row_ptr decreasing or outside [0, nnz] */
@@ -102,10 +102,11 @@ size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma);
  *               empty_offset with its per-tile start array.
  *
  * csr5_convert picks sigma itself, allocates with hipMalloc, runs on the default
- * stream, checks row_ptr[0] and row_ptr[m] on the host before it starts and
- * waits for the conversion's device-side checks at the end: it BLOCKS, and
- * returns CSR5_EINVAL (col_idx and val restored to CSR order) when row_ptr is
- * inconsistent or a column index is out of range.
+ * stream and waits for the conversion's device-side checks of the input
+ * (row_ptr[0] = 0, row_ptr[m] = nnz, non-decreasing; column indices in range):
+ * it BLOCKS, and returns CSR5_EINVAL (col_idx and val restored to CSR order)
+ * when one of them fails.  The conversion kernels stay inside the arrays
+ * whatever row_ptr holds.
  *
  * csr5_convert_ex: sigma = 0 means automatic.  If workspace != NULL the
  * handle's arrays are carved from it (workspace_bytes must be at least

@@ -1129,13 +1129,6 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     if (!geometry_fits(m, nnz, sigma)) return CSR5_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
-    if (!(flags & CSR5_FLAG_NO_HOST_CHECK)) {
-        IT ends[2] = {0, nnz};
-        if (hipMemcpyAsync(&ends[0], row_ptr, sizeof(IT), hipMemcpyDeviceToHost, s) != hipSuccess) return CSR5_EHIP;
-        if (hipMemcpyAsync(&ends[1], row_ptr + m, sizeof(IT), hipMemcpyDeviceToHost, s) != hipSuccess) return CSR5_EHIP;
-        if (hipStreamSynchronize(s) != hipSuccess) return CSR5_EHIP;
-        if (ends[0] != 0 || ends[1] != nnz) return CSR5_EINVAL;
-    }
 
     Geom g = make_geom(nnz, sigma);
     Layout L = make_layout(m, g, wide);

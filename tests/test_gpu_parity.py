@@ -125,9 +125,16 @@ def test_error_paths():
     assert rc == B.CSR5_EINVAL and not h
     rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr, None, d.val, check=False)
     assert rc == B.CSR5_EINVAL and not h
-    # nnz that does not match row_ptr[m]: caught by the host check
+    # nnz that does not match row_ptr[m]: caught by the device-side check of the last row
     rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz - 1, d.row_ptr, d.col_idx, d.val, check=False)
     assert rc == B.CSR5_EINVAL and not h
+    assert np.array_equal(d.col_idx.cpu().numpy(), a.col_idx) and np.array_equal(d.val.cpu().numpy(), a.val)
+    # row_ptr[0] != 0
+    d0 = DeviceCsr(a)
+    d0.row_ptr[0] = 1
+    rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz, d0.row_ptr, d0.col_idx, d0.val, check=False)
+    assert rc == B.CSR5_EINVAL and not h
+    assert np.array_equal(d0.col_idx.cpu().numpy(), a.col_idx)
     # workspace too small
     ws = torch.empty(256, dtype=torch.uint8, device="cuda:0")
     rc, h = B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val, sigma=4, workspace=ws, check=False)
