@@ -435,3 +435,48 @@ def edge_cases(T: int, seed: int = 7) -> list:
     out.append(identity(T + 13))
     out.append(permutation(2 * T + 1, seed))
     return out
+
+
+def structured_cases(T: int, seed: int = 11) -> list:
+    """Classic sparsity structures, sized around a tile of T nonzeros: arrowhead
+    (dense first row and column plus the diagonal), a band, dense diagonal blocks,
+    a dense upper triangle, and a matrix whose rows hold unsorted, repeated column
+    indices (a legal CSR matrix: repeated entries add up)."""
+    rng = np.random.default_rng(seed)
+    out = []
+
+    def from_coo(m, n, rows, cols, name, sort=True):
+        rows = np.asarray(rows, dtype=np.int64)
+        cols = np.asarray(cols, dtype=np.int64)
+        order = np.lexsort((cols, rows)) if sort else np.argsort(rows, kind="stable")
+        rows, cols = rows[order], cols[order]
+        lens = np.bincount(rows, minlength=m)
+        val = rng.uniform(-1, 1, size=rows.shape[0])
+        x = rng.uniform(-1, 1, size=n)
+        return _finish(m, n, lens, cols, val, x, name)
+
+    n = T + T // 2 + 3                                   # arrowhead: about 4.5 T nonzeros
+    i = np.arange(1, n)
+    out.append(from_coo(n, n, np.concatenate([np.zeros(n, np.int64), i, i]),
+                        np.concatenate([np.arange(n), np.zeros(n - 1, np.int64), i]), f"arrowhead_{n}"))
+    n = T // 2 + 7                                       # band of half-width 3
+    r = np.repeat(np.arange(n), 7)
+    c = r + np.tile(np.arange(-3, 4), n)
+    keep = (c >= 0) & (c < n)
+    out.append(from_coo(n, n, r[keep], c[keep], f"band7_{n}"))
+    b, nb = 24, max(2, (2 * T) // (24 * 24) + 1)         # dense 24 x 24 blocks on the diagonal
+    n = b * nb
+    r = np.repeat(np.arange(n), b)
+    c = (r // b) * b + np.tile(np.arange(b), n)
+    out.append(from_coo(n, n, r, c, f"blockdiag{b}_{n}"))
+    n = int(np.ceil(np.sqrt(2.0 * (T + T // 3))))        # dense upper triangle, a bit more than T nonzeros
+    r, c = np.triu_indices(n)
+    out.append(from_coo(n, n, r, c, f"upper_triangle_{n}"))
+    m, n = 200, 97                                       # unsorted columns with repeats
+    lens = rng.integers(0, 30, size=m)
+    r = np.repeat(np.arange(m), lens)
+    c = rng.integers(0, n, size=r.shape[0])
+    a = from_coo(m, n, r, c, "unsorted_repeated_columns", sort=False)
+    a.sorted_distinct = False
+    out.append(a)
+    return out

@@ -254,6 +254,20 @@ def test_side_stream_and_graph_replay():
     B.csr5_free(h)
 
 
+@pytest.mark.parametrize("sigma", [4, 16, 33])
+@pytest.mark.parametrize("wide", [False, True])
+def test_structured_cases(sigma, wide):
+    """Arrowhead, band, dense diagonal blocks, dense triangle, unsorted rows with
+    repeated column indices."""
+    for a in wl.structured_cases(64 * sigma):
+        say("structured", sigma, wide, a.name, a.m, a.n, a.nnz)
+        d = DeviceCsr(a, wide=wide)
+        h = convert(d, sigma=sigma)
+        check_format(d, h, (a.name, sigma))
+        check_spmv(d, h, (a.name, sigma))
+        B.csr5_free(h)
+
+
 def test_conversion_in_a_graph():
     """With a workspace and CSR5_FLAG_NO_HOST_CHECK the conversion only enqueues
     kernels (no allocation, no memset, no wait), so conversion + SpMV can be

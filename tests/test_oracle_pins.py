@@ -20,7 +20,7 @@ def coo_rows(a):
 
 
 def small_cases(T):
-    return wl.edge_cases(T) + [wl.tiny_uniform(m=300, n=200, max_len=12, seed=5)]
+    return wl.edge_cases(T) + wl.structured_cases(T) + [wl.tiny_uniform(m=300, n=200, max_len=12, seed=5)]
 
 
 # ----------------------------------------------------------------- Algorithm 1

@@ -16,10 +16,11 @@ def check_structure(a):
     assert a.col_idx.shape == (a.nnz,) and a.val.shape == (a.nnz,) and a.x.shape == (a.n,)
     if a.nnz:
         assert a.col_idx.min() >= 0 and a.col_idx.max() < a.n
-        inc = np.diff(a.col_idx.astype(np.int64)) > 0
-        starts = np.zeros(a.nnz, dtype=bool)
-        starts[a.row_ptr[:-1][lens > 0]] = True
-        assert np.all(inc | starts[1:]), "columns must be sorted and distinct inside every row"
+        if getattr(a, "sorted_distinct", True):
+            inc = np.diff(a.col_idx.astype(np.int64)) > 0
+            starts = np.zeros(a.nnz, dtype=bool)
+            starts[a.row_ptr[:-1][lens > 0]] = True
+            assert np.all(inc | starts[1:]), "columns must be sorted and distinct inside every row"
     assert np.all(np.isfinite(a.val)) and np.all(np.isfinite(a.x))
 
 
@@ -98,3 +99,23 @@ def test_edge_case_catalogue():
     assert by["one_long_row"].m == 1 and by["one_long_row"].nnz > 3 * T
     assert by["exact_two_tiles"].nnz == 2 * T
     assert by["less_than_one_tile"].nnz < T
+
+
+def test_structured_case_catalogue():
+    T = 64 * 4
+    cases = wl.structured_cases(T)
+    by = {c.name.split("_")[0]: c for c in cases}
+    for a in cases:
+        check_structure(a)
+        assert digest(a) == digest({c.name: c for c in wl.structured_cases(T)}[a.name])
+    arrow = by["arrowhead"]
+    lens = np.diff(arrow.row_ptr)
+    assert lens[0] == arrow.n and np.all(lens[1:] == 2) and arrow.nnz > 4 * T
+    band = by["band7"]
+    assert np.diff(band.row_ptr).max() == 7 and np.diff(band.row_ptr).min() == 4
+    tri = by["upper"]
+    assert np.array_equal(np.diff(tri.row_ptr), np.arange(tri.n, 0, -1)) and tri.nnz > T
+    rep = by["unsorted"]
+    assert not rep.sorted_distinct
+    r = np.repeat(np.arange(rep.m), np.diff(rep.row_ptr))
+    assert np.unique(np.stack([r, rep.col_idx]), axis=1).shape[1] < rep.nnz          # it does repeat entries
