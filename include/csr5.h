@@ -136,6 +136,23 @@ int csr5_spmv(csr5_handle_t h, const double *x, double *y);
 int csr5_spmv_ex(csr5_handle_t h, const double *x, double *y, void *hip_stream);
 
 /*
+ * For callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): csr5_spmv_ex with the auxiliary array
+ * of the cross-tile sums taken from a fixed array in the library's device image
+ * (CSR5_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead of
+ * the handle's own.  No hipMalloc, hipFree or other allocating call is made.
+ * Same arguments, same result and same error codes as csr5_spmv_ex (double
+ * precision, either index width), plus CSR5_ERANGE when the handle has more than
+ * CSR5_STATIC_MAX_TILES tiles (p, the incomplete tile included).  Every slot the
+ * second kernel reads has been written by the first, so nothing needs clearing
+ * between calls.  All calls on one GPU share the array, whatever their handle:
+ * calls that overlap in time on one GPU race; order them (one stream, or events).
+ */
+#define CSR5_STATIC_SCRATCH_BYTES (4u << 20)
+#define CSR5_STATIC_MAX_TILES (CSR5_STATIC_SCRATCH_BYTES / 8u - 1u)
+int csr5_spmv_static(csr5_handle_t h, const double *x, double *y, void *hip_stream);
+
+/*
  * Single-precision variant (the paper's Figure 3 is single precision): same
  * format, same kernels instantiated for float.  val, x and y are float arrays;
  * a handle made by csr5s_convert_ex is accepted by csr5s_spmv_ex,

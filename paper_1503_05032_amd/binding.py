@@ -20,6 +20,8 @@ LIB_PATH = os.path.join(_PKG, "libcsr5.so")
 
 CSR5_OK, CSR5_EINVAL, CSR5_ENOMEM, CSR5_EHIP, CSR5_ERANGE = 0, -1, -2, -3, -4
 CSR5_OMEGA, CSR5_SIGMA_MIN, CSR5_SIGMA_MAX = 64, 1, 48
+CSR5_STATIC_SCRATCH_BYTES = 4 << 20
+CSR5_STATIC_MAX_TILES = CSR5_STATIC_SCRATCH_BYTES // 8 - 1
 CSR5_FLAG_NONE, CSR5_FLAG_NO_HOST_CHECK = 0, 1
 CSR5_STATUS_BAD_ROW_PTR, CSR5_STATUS_BAD_COL_IDX, CSR5_STATUS_HAS_DIRTY = 1, 2, 4
 CSR5_STATUS_HAS_EMPTY_ROWS = 8
@@ -28,7 +30,7 @@ CSR5_ARRAY_TILE_PTR, CSR5_ARRAY_TILE_DESC, CSR5_ARRAY_EMPTY_OFFSET_PTR, CSR5_ARR
 # every symbol include/csr5.h declares
 SYMBOLS = [
     "csr5_sigma_auto", "csr5_workspace_bytes", "csr5_convert", "csr5_convert_ex", "csr5_spmv",
-    "csr5_spmv_ex", "csr5_spmv_profile", "csr5_to_csr", "csr5_free", "csr5_status", "csr5_get_info", "csr5_get_arrays",
+    "csr5_spmv_ex", "csr5_spmv_static", "csr5_spmv_profile", "csr5_to_csr", "csr5_free", "csr5_status", "csr5_get_info", "csr5_get_arrays",
     "csr5_read_array", "csr5_strerror", "csr5_baseline_csr_scalar", "csr5_baseline_csr_vector",
     "csr5s_convert_ex", "csr5s_spmv_ex", "csr5s_spmv_profile",
     "csr5l_workspace_bytes", "csr5l_convert_ex", "csr5l_get_arrays",
@@ -80,6 +82,8 @@ def load():
     lib.csr5_spmv.argtypes = [vp, vp, vp]
     lib.csr5_spmv_ex.restype = C.c_int
     lib.csr5_spmv_ex.argtypes = [vp, vp, vp, vp]
+    lib.csr5_spmv_static.restype = C.c_int
+    lib.csr5_spmv_static.argtypes = [vp, vp, vp, vp]
     lib.csr5_spmv_profile.restype = C.c_int
     lib.csr5_spmv_profile.argtypes = [vp, vp, vp, vp, C.c_int, C.POINTER(C.c_float)]
     lib.csr5_to_csr.restype = C.c_int
@@ -213,6 +217,11 @@ def csr5_spmv(h, x, y, check=True):
 
 def csr5_spmv_ex(h, x, y, stream=None, check=True):
     return _chk(load().csr5_spmv_ex(h, _ptr(x), _ptr(y), _stream(stream)), "csr5_spmv_ex", check)
+
+
+def csr5_spmv_static(h, x, y, stream=None, check=True):
+    """csr5_spmv_ex without any allocation: the cross-tile array is the library's static one."""
+    return _chk(load().csr5_spmv_static(h, _ptr(x), _ptr(y), _stream(stream)), "csr5_spmv_static", check)
 
 
 def csr5_spmv_profile(h, x, y, reps, stream=None):

@@ -8,6 +8,7 @@
 // kernel.  The C ABI is declared in include/csr5.h.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <new>
 #include <type_traits>
@@ -1009,6 +1010,39 @@ k_csr_vector(int m, const int32_t* __restrict__ row_ptr, const int32_t* __restri
 }  // namespace
 
 // ----------------------------------------------------------------------------
+// Scratch of csr5_spmv_static, the SpMV entry point that allocates nothing: the
+// cross-tile auxiliary array lives here instead of in the handle.  Every GPU the
+// library runs on holds its own copy of this array until the process ends.  In
+// host code the array's NAME is only a stand-in; the memory is reached through
+// the address hipGetSymbolAddress returns for the current device, resolved once
+// per device (static_scratch) and passed to the kernels as an argument.
+// ----------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[CSR5_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> scratch_ptr[MAX_DEVICES];
+
+// Address of `scratch` on device `dev`, which must be the current device.
+// Threads that race here resolve the same address.
+int static_scratch(int dev, void** out) {
+    if (dev < 0 || dev >= MAX_DEVICES) return CSR5_ERANGE;
+    void* p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return CSR5_EHIP;
+        }
+        scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return CSR5_OK;
+}
+
+}  // namespace
+
+// ----------------------------------------------------------------------------
 // handle
 // ----------------------------------------------------------------------------
 struct csr5_handle_s {
@@ -1168,6 +1202,11 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         return CSR5_EHIP;
     }
     h->in_csr5_order = true;
+    {   // set-up time on this device: resolve the static scratch's address now, so
+        // that csr5_spmv_static has nothing left to look up (failure is reported there)
+        void* unused = nullptr;
+        (void)static_scratch(h->device, &unused);
+    }
     tp_t* const tile_ptr = static_cast<tp_t*>(h->tile_ptr);
     IT* const eop = static_cast<IT*>(h->eop);
 
@@ -1279,13 +1318,13 @@ int csr5_convert(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int3
 constexpr int LAUNCH_TILES = 1, LAUNCH_FIXUP = 2, LAUNCH_BOTH = 3;
 
 template <typename VT, typename IT>
-static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, int which) {
+static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, int which, void* carry_mem) {
     using tp_t = typename Index<IT>::tp_t;
     const IT* row_ptr = static_cast<const IT*>(h->row_ptr);
     const tp_t* tile_ptr = static_cast<const tp_t*>(h->tile_ptr);
     const IT* eop = static_cast<const IT*>(h->eop);
     hipError_t e = hipSuccess;
-    VT* carry = static_cast<VT*>(h->carry);
+    VT* carry = static_cast<VT*>(carry_mem ? carry_mem : h->carry);
     if (h->nnz > 0 && (which & LAUNCH_TILES)) {
         switch (h->g.sigma) {
 #define X(S) case S: e = launch_spmv<S, VT, IT>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, eop, \
@@ -1314,16 +1353,17 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, in
 
 // The 64-bit index variant exists for double only.
 template <typename VT>
-static int spmv_launch(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, int which = LAUNCH_BOTH) {
+static int spmv_launch(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, int which = LAUNCH_BOTH,
+                       void* carry_mem = nullptr) {
     if constexpr (std::is_same<VT, double>::value) {
-        if (h->wide) return spmv_launch_it<double, int64_t>(h, x, y, s, which);
+        if (h->wide) return spmv_launch_it<double, int64_t>(h, x, y, s, which, carry_mem);
     }
     if (h->wide) return CSR5_EINVAL;
-    return spmv_launch_it<VT, int32_t>(h, x, y, s, which);
+    return spmv_launch_it<VT, int32_t>(h, x, y, s, which, carry_mem);
 }
 
 template <typename VT>
-static int spmv_checked(csr5_handle_t h, const VT* x, VT* y, void* hip_stream) {
+static int spmv_checked(csr5_handle_t h, const VT* x, VT* y, void* hip_stream, bool static_carry = false) {
     constexpr int want = std::is_same<VT, float>::value ? CSR5_DTYPE_F32 : CSR5_DTYPE_F64;
     if (!h || !h->in_csr5_order || h->dtype != want) return CSR5_EINVAL;
     int dev = -1;
@@ -1331,8 +1371,15 @@ static int spmv_checked(csr5_handle_t h, const VT* x, VT* y, void* hip_stream) {
     if (dev != h->device) return CSR5_EINVAL;              // the handle's arrays live on another device
     if (h->m > 0 && !y) return CSR5_EINVAL;
     if (h->nnz > 0 && !x) return CSR5_EINVAL;
+    void* carry_mem = nullptr;
+    if (static_carry) {
+        // one 8-byte slot per tile, the incomplete one included, in the static array
+        if ((size_t(h->g.p) + 1) * 8 > size_t(CSR5_STATIC_SCRATCH_BYTES)) return CSR5_ERANGE;
+        const int rc = static_scratch(dev, &carry_mem);
+        if (rc != CSR5_OK) return rc;
+    }
     if (h->m == 0) return CSR5_OK;
-    return spmv_launch<VT>(h, x, y, static_cast<hipStream_t>(hip_stream));
+    return spmv_launch<VT>(h, x, y, static_cast<hipStream_t>(hip_stream), LAUNCH_BOTH, carry_mem);
 }
 
 template <typename VT>
@@ -1375,6 +1422,9 @@ int csr5_spmv_ex(csr5_handle_t h, const double* x, double* y, void* hip_stream) 
     return spmv_checked<double>(h, x, y, hip_stream);
 }
 int csr5_spmv(csr5_handle_t h, const double* x, double* y) { return spmv_checked<double>(h, x, y, nullptr); }
+int csr5_spmv_static(csr5_handle_t h, const double* x, double* y, void* hip_stream) {
+    return spmv_checked<double>(h, x, y, hip_stream, true);
+}
 int csr5s_spmv_ex(csr5_handle_t h, const float* x, float* y, void* hip_stream) {
     return spmv_checked<float>(h, x, y, hip_stream);
 }
