@@ -230,6 +230,7 @@ def measure(P, sigma_arg, steps, warmup, headline, quick):
         ws_c = torch.empty(wsb, dtype=torch.uint8, device=dev)
         h_c = P.convert_ex(m, n, nnz, rp_c, col_c, val_c, sigma=sigma, workspace=ws_c,
                            flags=B.CSR5_FLAG_NO_HOST_CHECK)
+        assert B.csr5_status(h_c) & 3 == 0      # also lets the handle learn which launches the matrix needs
         keep.append((rp_c, col_c, val_c, ws_c))
         rot.append((h_c, x_c, y_c))
     torch.cuda.synchronize()

@@ -76,9 +76,12 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * nnz nonzeros at the given sigma (0 = the value csr5_sigma_auto picks).  An
  * upper bound computable on the host: tile_ptr (p+1 words) + tile_desc
  * (p_c*W*64 words) + empty_offset_ptr (p_c+1 words) + empty_offset (at most
- * min(m + p_c, p_c*T) words) + the SpMV's auxiliary array (p+1 doubles) + the
- * conversion's scan scratch (p_c/8192 + 1 words) + a status word, each rounded
- * up to 256 bytes.
+ * min(m + p_c, p_c*T) words) + the SpMV's auxiliary array (p+1 doubles) + one
+ * word per tile saying how far into its first row the tile starts (p+1) + for
+ * sigma >= 8 a copy of every complete tile's last 32 (col_idx, val) pairs in CSR
+ * order (384 bytes per tile; it lets a tile finish a row that began in the
+ * previous tile without a second kernel) + the conversion's scan scratch
+ * (p_c/8192 + 1 words) + a status word, each rounded up to 256 bytes.
  * Returns 0 for invalid arguments.
  */
 size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma);
@@ -123,14 +126,25 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, i
                     void *hip_stream, uint32_t flags, csr5_handle_t *out);
 
 /*
- * y = A*x (Section 4: Algorithm 8 per complete tile; a tile's first segment,
- * when it continues a row of an earlier tile, goes through an auxiliary array
- * that a second small kernel adds to y; the entries after the last complete
- * tile by a row-wise SIMD reduction).  x double[n], y double[m]; y is
- * overwritten (rows without nonzeros get 0).  x and y must not overlap.
- * Asynchronous.  Summation order differs from CSR order.  The auxiliary array
- * lives in the handle: calls on ONE handle must not overlap in time (use one
- * stream, or order them).
+ * y = A*x (Section 4: Algorithm 8 per complete tile; the entries after the last
+ * complete tile by a row-wise SIMD reduction).  A tile's first segment, when it
+ * continues a row of an earlier tile, is completed in one of two ways, fixed per
+ * matrix at conversion: if no tile starts more than 32 entries into a row
+ * (sigma >= 8), every tile re-reads the head of its first row and stores the
+ * finished row, and the SpMV is ONE kernel; otherwise those segments go through
+ * an auxiliary array that a second small kernel adds to y (Section 4's "global
+ * auxiliary array").  Which of the two, and whether rows without nonzeros need
+ * their zeros written, is in the conversion's status word: the library launches
+ * only what the matrix needs once the host has seen that word (csr5_convert and
+ * csr5_convert_ex without CSR5_FLAG_NO_HOST_CHECK read it; after an asynchronous
+ * conversion call csr5_status once), and everything until then -- same result,
+ * a few microseconds slower.
+ * x double[n], y double[m]; y is overwritten (rows without nonzeros get 0).  x
+ * and y must not overlap.  Asynchronous.  Summation order differs from CSR
+ * order; rows summed through the auxiliary array by more than one wavefront and
+ * rows cut inside the incomplete tile are added up atomically, so their last
+ * bits may differ between runs.  The auxiliary array lives in the handle: calls
+ * on ONE handle must not overlap in time (use one stream, or order them).
  */
 int csr5_spmv(csr5_handle_t h, const double *x, double *y);
 int csr5_spmv_ex(csr5_handle_t h, const double *x, double *y, void *hip_stream);
@@ -214,6 +228,8 @@ int csr5_free(csr5_handle_t h);
  * Waits for the conversion's stream and returns the device-side status word
  * (CSR5_STATUS_* bits) in *status (host).  BAD_* bits mean the input violated
  * the contract; results are then undefined (but conversion stays in bounds).
+ * The handle remembers what it read: later csr5_spmv* calls launch only the
+ * kernels this matrix needs.
  */
 int csr5_status(csr5_handle_t h, uint32_t *status);
 

@@ -24,6 +24,26 @@ constexpr uint32_t BAD_BITS = CSR5_STATUS_BAD_ROW_PTR | CSR5_STATUS_BAD_COL_IDX;
 // empty_offset layout has to be scanned.  Set by k_tile_desc only; the scan
 // kernels decide on it, and nothing in their own launches changes it.
 constexpr uint32_t STATUS_SCAN_NEEDED = 1u << 16;
+// Internal status bit: some tile (the incomplete one included) starts more than
+// LOOK entries into a row, so the SpMV needs its second kernel (see k_spmv).
+constexpr uint32_t STATUS_NEEDS_CARRY = 1u << 17;
+// A tile whose first segment continues a row that began at most LOOK entries
+// before the tile fetches those entries itself, from a copy of every tile's last
+// LOOK entries that the conversion keeps in CSR order next to the format (in the
+// transposed tile they are spread over sigma cache lines each for val and
+// col_idx; re-reading them there cost 16 % more memory traffic).  LOOK = 32 is
+// three cache lines per tile, read by every tile without first asking how long
+// its head is (a dependent load at that point costs more than the lines); 384
+// bytes per tile, not kept for sigma < LOOK_MIN_SIGMA, where it would be a large
+// part of the matrix (those matrices always take the auxiliary-array path).
+constexpr int LOOK = 32;
+constexpr int LOOK_MIN_SIGMA = 8;
+// One record per tile: LOOK values (8 bytes each, 4 used in single precision)
+// followed by LOOK column indices, contiguous, so that a tile fetches it with one
+// run of three cache lines.  Strides of the two views of the record array:
+constexpr int LAST_REC_BYTES = LOOK * 8 + LOOK * 4;
+constexpr int LAST_COL_STRIDE = LAST_REC_BYTES / 4;           // in int32
+template <typename VT> constexpr int last_val_stride() { return LAST_REC_BYTES / int(sizeof(VT)); }
 constexpr uint32_t STATUS_PUBLIC = 0xffu;
 constexpr int NUM_XCD = 8;  // MI355X: 8 accelerator dies, each with its own L2
 
@@ -148,12 +168,13 @@ __device__ __forceinline__ uint32_t xcd_order(uint32_t w, uint32_t nb, uint32_t 
 // ----------------------------------------------------------------------------
 // Conversion step 2a: tile_ptr (Algorithm 4, first loop).  One thread per
 // tile boundary.  The same launch clears the flag words the next kernel ORs
-// into, and the status word.
+// into, and the status word, and notes for every tile how many entries of its
+// first row lie before it (tile_head, an auxiliary array of the SpMV).
 // ----------------------------------------------------------------------------
 template <typename IT>
 __global__ void __launch_bounds__(256)
 k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p,
-           typename Index<IT>::tp_t* __restrict__ tile_ptr,
+           typename Index<IT>::tp_t* __restrict__ tile_ptr, uint32_t* __restrict__ tile_head,
            uint32_t* __restrict__ desc, size_t ndesc, uint32_t* __restrict__ status) {
     using tp_t = typename Index<IT>::tp_t;
     size_t gid = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -162,7 +183,14 @@ k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p,
     if (gid == 0) *status = 0u;
     for (size_t t = gid; t <= size_t(p); t += stride) {
         int64_t bnd = int64_t(t) * T;
-        tile_ptr[t] = tp_t(count_le(row_ptr, m + 1, bnd) - 1) & Index<IT>::ROWMASK;
+        const int row = count_le(row_ptr, m + 1, bnd) - 1;
+        tile_ptr[t] = tp_t(row) & Index<IT>::ROWMASK;
+        // how far into its first row the tile starts (0: the row starts with the
+        // tile), saturated at LOOK + 1: what the SpMV needs to know about the
+        // boundary, so that it does not have to look into row_ptr itself
+        int64_t head = 0;
+        if (t < size_t(p) && row >= 0 && row < m) head = bnd - int64_t(row_ptr[row]);
+        tile_head[t] = uint32_t(head < 0 ? 0 : (head > LOOK + 1 ? LOOK + 1 : head));
     }
 }
 
@@ -202,6 +230,10 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
     // nonzero mark no tile, and row 0 speaks for them.
     const bool empty = in && !bad && a == b;
     if (empty && r == 0) raise_status(status, CSR5_STATUS_HAS_EMPTY_ROWS);
+    // Does some tile start more than LOOK entries into this row?  The last tile
+    // boundary inside the row is the farthest from its start.
+    const bool far = in && !bad && a != b && ((int64_t(b) - 1) / T) * T - int64_t(a) > LOOK;
+    if (__ballot(far) != 0ull && lane == 0) raise_status(status, STATUS_NEEDS_CARRY);
     const int t = (empty && a > 0) ? int((a - 1) / T) : -1 - lane;
     const int tprev = __shfl_up(t, 1, OMEGA);
     if (t >= 0 && t < p && (lane == 0 || tprev != t) &&
@@ -487,7 +519,8 @@ k_empty_offset(int m, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
 // lane happens to write exactly the addresses it read.  LDS rows are padded to
 // an odd pitch to avoid bank conflicts on the strided LDS read.  BACK = the
 // inverse permutation (CSR5 -> CSR, Section 3.6).  The last block also checks
-// the column indices of the incomplete tile.
+// the column indices of the incomplete tile.  The forward pass also keeps a copy
+// of every tile's last LOOK entries in CSR order when asked to.
 // ----------------------------------------------------------------------------
 template <int SIGMA>
 struct TransposeShape {
@@ -507,7 +540,7 @@ __device__ __forceinline__ void wave_sync_lds() {
 template <int SIGMA, bool BACK, typename VT>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
 k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __restrict__ val,
-            uint32_t* __restrict__ status) {
+            uint32_t* __restrict__ status, int32_t* __restrict__ last_col, VT* __restrict__ last_val) {
     constexpr int T = OMEGA * SIGMA;
     constexpr int PITCH = TransposeShape<SIGMA>::PITCH;
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
@@ -525,6 +558,8 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
     if (active) {
 #pragma unroll
         for (int k = 0; k < SIGMA; k++) v[k] = __builtin_nontemporal_load(&val[base + k * OMEGA + lane]);
+        // the tile's last LOOK entries, still in CSR order, for the SpMV's look-behind
+        if (!BACK && last_val && lane >= OMEGA - LOOK) last_val[size_t(tile) * last_val_stride<VT>() + (lane - (OMEGA - LOOK))] = v[SIGMA - 1];
         if (!BACK) {
 #pragma unroll
             for (int k = 0; k < SIGMA; k++) {
@@ -560,6 +595,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
             c[k] = __builtin_nontemporal_load(&col_idx[base + k * OMEGA + lane]);
             bad |= (c[k] < 0) | (c[k] >= n);
         }
+        if (!BACK && last_col && lane >= OMEGA - LOOK) last_col[size_t(tile) * LAST_COL_STRIDE + (lane - (OMEGA - LOOK))] = c[SIGMA - 1];
         if (!BACK) {
 #pragma unroll
             for (int k = 0; k < SIGMA; k++) {
@@ -617,21 +653,57 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
 // Cross-tile (Section 4 offers atomic adds or a global auxiliary array; device
 // wide fp64 atomics are resolved on the memory side of the eight L2s on this
 // chip and, at two per tile, measured slower than everything else in the kernel
-// together, so the auxiliary array it is).  Only segment 0 of a tile can
-// continue a row that an earlier tile opened (it does iff the tile's first
-// nonzero is not its row's first: row_ptr[tile_ptr] != tile*T).  Such a
-// continuation goes to carry[tile]; every other segment, including the tile's
-// last, is a plain store: the tile holds that row's first nonzero, so it writes
-// the row's base value, and k_spmv_fixup adds the carries afterwards.  y needs
-// no zero-fill and the result does not depend on scheduling.
+// together).  Only segment 0 of a tile can continue a row that an earlier tile
+// opened (it does iff the tile's first nonzero is not its row's first:
+// row_ptr[tile_ptr] != tile*T).  Two ways, chosen per MATRIX during conversion
+// (status word), so that both tiles at a boundary decide alike without talking
+// to each other:
+//  * no tile starts more than LOOK = 32 entries into a row: every tile reads the
+//    head of its first row itself (at most 32 entries of the previous tile, from
+//    a CSR-order copy of each tile's last 32 entries; one extra gather), adds it
+//    to its segment 0 and stores the finished row; the previous tile does not
+//    store its last segment.  Such a matrix needs no second kernel at all.
+//  * otherwise: the auxiliary array.  Segment 0 goes to carry[tile]; the tile that
+//    holds the row's first nonzero stores the row's base value, and k_spmv_fixup
+//    adds the carries afterwards.
+// y needs no zero-fill.  Rows that receive carries from more than one wavefront
+// of k_spmv_fixup, and rows cut by 64-entry chunks of the incomplete tile, are
+// summed with atomic adds, in whatever order they arrive: their last bits can
+// differ from run to run.  Everything else is summed in a fixed order.
 //
 // Workgroup 0 handles the entries after the last complete tile when there are
-// any (early, so that its dependent searches hide behind the tiles).
+// any (early, so that its dependent searches hide behind the tiles); workgroups
+// after the tiles write the zeros of rows without nonzeros when the matrix has
+// such rows.
 // ----------------------------------------------------------------------------
 template <int SIGMA>
 struct FlagWord {
     using type = typename std::conditional<(SIGMA > 32), uint64_t, uint32_t>::type;
 };
+
+// Sum over the 64 lanes; every lane gets the total.
+template <typename VT>
+__device__ __forceinline__ VT wave_sum(VT v) {
+#pragma unroll
+    for (int d = OMEGA / 2; d >= 1; d >>= 1) v += __shfl_xor(v, d, OMEGA);
+    return v;
+}
+
+// The last `count` (<= LOOK) entries of a complete tile, read from the CSR-order
+// copy of its last LOOK entries: lane k multiplies entry LOOK - count + k by its x
+// and the wavefront sums the products.  This is how the incomplete tile's
+// workgroup completes a row that began shortly before it, instead of handing its
+// part to a second kernel (the complete tiles do the same inside k_spmv).
+template <typename VT>
+__device__ __forceinline__ VT look_behind(const int32_t* __restrict__ last_col, const VT* __restrict__ last_val,
+                                          const VT* __restrict__ x, int count, int lane) {
+    VT prod = VT(0);
+    if (lane < count) {
+        const int at = LOOK - count + lane;
+        prod = last_val[at] * x[last_col[at]];
+    }
+    return wave_sum(prod);
+}
 
 constexpr int TAIL_MAX_CHUNKS = (CSR5_SIGMA_MAX * OMEGA) / OMEGA + 1;   // 64-entry chunks in < one tile
 
@@ -642,12 +714,14 @@ constexpr int TAIL_MAX_CHUNKS = (CSR5_SIGMA_MAX * OMEGA) / OMEGA + 1;   // 64-en
 // stored directly.  A row cut by a chunk boundary is accumulated in LDS, in the
 // slot of the chunk it starts in (at most one row starts in a chunk and leaves
 // it), and stored at the end.  The part of a row that began in the complete
-// tiles goes to carry[pc] like a tile's segment 0.
+// tiles is treated like a tile's segment 0: completed here when the row began at
+// most LOOK entries earlier, handed to carry[pc] otherwise.
 template <typename VT, typename IT>
 __device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
                           const IT* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                           const VT* __restrict__ val, const VT* __restrict__ x,
-                          VT* __restrict__ y, VT* __restrict__ carry_slot) {
+                          VT* __restrict__ y, VT* __restrict__ carry_slot,
+                          const int32_t* __restrict__ last_col, const VT* __restrict__ last_val) {
     __shared__ VT acc[TAIL_MAX_CHUNKS];
     __shared__ int acc_row[TAIL_MAX_CHUNKS];
     __shared__ VT acc_first;
@@ -696,17 +770,29 @@ __device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
     __syncthreads();
     for (int q = threadIdx.x; q < TAIL_MAX_CHUNKS; q += blockDim.x)
         if (acc_row[q] >= 0) y[acc_row[q]] = acc[q];
-    if (threadIdx.x == 0) *carry_slot = acc_first;
+    if (threadIdx.x < OMEGA) {                           // first wavefront
+        VT carried = acc_first;
+        if (last_col && row_lo < m && first > 0) {       // last_col: entries of the last complete tile, or null
+            const IT rs = row_ptr[row_lo];
+            if (rs < first && first - rs <= IT(LOOK)) {  // the first row began shortly before: finish it here
+                const VT head = look_behind<VT>(last_col, last_val, x, int(first - rs), lane);
+                if (lane == 0) y[row_lo] = head + acc_first;
+                carried = VT(0);
+            }
+        }
+        if (lane == 0) *carry_slot = carried;
+    }
 }
 
-template <int SIGMA, typename VT, typename IT>
+template <int SIGMA, typename VT, typename IT, bool CAN_LOOK>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
-k_spmv(int m, IT nnz, int pc, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd_chunk,
+k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd_chunk,
        const IT* __restrict__ row_ptr, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
        const uint32_t* __restrict__ tile_desc, const IT* __restrict__ eop,
        const int32_t* __restrict__ eo, const int32_t* __restrict__ col_idx,
        const VT* __restrict__ val, const VT* __restrict__ x, VT* __restrict__ y,
-       VT* __restrict__ carry, const uint32_t* __restrict__ status) {
+       VT* __restrict__ carry, const uint32_t* __restrict__ status, const uint32_t* __restrict__ tile_head,
+       const int32_t* __restrict__ last_col, const VT* __restrict__ last_val) {
     constexpr int T = OMEGA * SIGMA;
     constexpr int YBITS = 32 - __builtin_clz(uint32_t(T - 1));        // ceil(log2(64*sigma))
     constexpr int W = (SIGMA + SBITS + YBITS + 31) / 32;
@@ -718,18 +804,45 @@ k_spmv(int m, IT nnz, int pc, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd
     __shared__ double lds[WAVES][OMEGA * PITCH];
 
     const uint32_t st = *status;      // consulted below, after the streaming loads are in flight
+    // Rows that cross a tile boundary are completed by look-behind in the whole
+    // matrix or nowhere: both tiles at a boundary must decide alike.
+    // CAN_LOOK = false is the instantiation for matrices the host knows to need
+    // the carry array: the same kernel without the look-behind's loads.
+    const bool look = CAN_LOOK && last_col != nullptr && !(st & STATUS_NEEDS_CARRY);
 
     if (blockIdx.x < has_tail) {      // workgroup 0: incomplete last tile
         if (st & BAD_BITS) return;
         const tp_t first_row = tile_ptr[pc] & Index<IT>::ROWMASK;
         spmv_tail<VT, IT>(m, nnz, IT(pc) * T, first_row > tp_t(m) ? uint32_t(m) : uint32_t(first_row),
-                          row_ptr, col_idx, val, x, y, carry + pc);
+                          row_ptr, col_idx, val, x, y, carry + pc,
+                          (look && pc > 0) ? last_col + size_t(pc - 1) * LAST_COL_STRIDE : nullptr,
+                          (look && pc > 0) ? last_val + size_t(pc - 1) * last_val_stride<VT>() : nullptr);
+        return;
+    }
+    if (blockIdx.x >= has_tail + nb_tiles) {   // workgroups after the tiles: the zeros of rows without nonzeros
+        if ((st & BAD_BITS) || !(st & CSR5_STATUS_HAS_EMPTY_ROWS)) return;
+        const uint32_t b = blockIdx.x - has_tail - nb_tiles, nb = gridDim.x - has_tail - nb_tiles;
+        const int64_t stride = int64_t(nb) * blockDim.x;
+        for (int64_t r = int64_t(b) * blockDim.x + threadIdx.x; r < int64_t(m); r += stride)
+            if (row_ptr[r] == row_ptr[r + 1]) y[r] = VT(0);
         return;
     }
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / OMEGA);
     const int tile = int(xcd_order(blockIdx.x - has_tail, nb_tiles, xcd_chunk)) * WAVES + wave;
     if (tile >= pc) return;
+
+    // ---- look-behind, first part: the previous tile's last LOOK entries, whether
+    // or not this tile turns out to need them (asking first would put a dependent
+    // load in front of these, and everything the wavefront loads later waits for
+    // them in turn).  Lanes LOOK.. repeat the addresses of lanes 0..LOOK-1.
+    VT head_v = VT(0), head_x = VT(0);
+    int32_t head_c = 0;
+    if constexpr (CAN_LOOK) {
+        const size_t rec = size_t(tile > 0 ? tile - 1 : 0);
+        head_c = last_col[rec * LAST_COL_STRIDE + size_t(lane & (LOOK - 1))];
+        head_v = last_val[rec * last_val_stride<VT>() + size_t(lane & (LOOK - 1))];
+    }
 
     // ---- stream the tile.  val: at step j the 64 lanes read 64 consecutive
     // doubles, lane i keeping entry (column i, step j).  col_idx is not needed by
@@ -773,8 +886,19 @@ k_spmv(int m, IT nnz, int pc, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd
         nseg_t = uint32_t(e1 - e0);
     }
     if ((st & BAD_BITS) || row0_wide >= tp_t(m)) return;  // rejected input: gather and store nothing
-    // does segment 0 continue a row that an earlier tile opened?
-    const bool cont0 = row_ptr[row0] != IT(tile) * T;
+    // Does segment 0 continue a row that an earlier tile opened?  (tile_head:
+    // entries of the tile's first row that lie before the tile, saturated.)  Then
+    // either this tile fetches the row's head (at most LOOK entries, see `look`)
+    // and stores the finished row, or its part goes through the carry array.
+    // The mirror image: when the next tile (or the incomplete tile's workgroup)
+    // completes this tile's last row, this tile must not store its part of it.
+    const uint32_t head_len = tile_head[tile];
+    const uint32_t next_head = tile_head[tile + 1];           // p + 1 entries; 0 at p
+    const bool cont0 = head_len != 0;
+    const bool skip_last = look && next_head != 0;
+    const bool fetch_head = look && cont0 && head_len <= uint32_t(LOOK);   // uniform; the length test cannot fail
+    // the head is the last head_len of those LOOK entries
+    const bool head_lane = fetch_head && lane < LOOK && lane >= LOOK - int(head_len);
 
     // ---- gather x.  Lane i owns the CSR entries i*sigma .. i*sigma+sigma-1 of the
     // tile, so at a fixed step the 64 lanes would gather from 64 unrelated
@@ -809,6 +933,7 @@ k_spmv(int m, IT nnz, int pc, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd
         wave_sync_lds();
 #pragma unroll
         for (int k = 0; k < SIGMA; k++) xv[k] = x[c[k]];
+        if constexpr (CAN_LOOK) head_x = x[head_c];
 #pragma unroll
         for (int k = 0; k < SIGMA; k++) {
             const int e = k * OMEGA + lane;
@@ -862,31 +987,36 @@ k_spmv(int m, IT nnz, int pc, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd
     if (dirty && nseg > nseg_t) nseg = nseg_t;            // cannot happen for a consistent format
     wave_sync_lds();
 
+    VT head = VT(0);
+    if constexpr (CAN_LOOK) head = wave_sum(head_lane ? head_v * head_x : VT(0));
+
     // ---- write the tile's rows.  Segment s is row tile_ptr + s, or
     // tile_ptr + empty_offset[s] when the tile holds empty rows.  Segment 0 goes
     // to the carry array when it continues an earlier tile's row.
     for (uint32_t s0 = 0; s0 < nseg; s0 += OMEGA) {
         const uint32_t sg = s0 + lane;
         if (sg < nseg) {
-            const VT value = yb[sg];
+            VT value = yb[sg];
             const uint32_t row = row0 + (dirty ? uint32_t(eo_t[sg]) : sg);
-            if (sg == 0) carry[tile] = cont0 ? value : VT(0);
-            if ((sg != 0 || !cont0) && row < uint32_t(m)) y[row] = value;
+            if (sg == 0) {
+                carry[tile] = (cont0 && !look) ? value : VT(0);
+                value += head;                             // 0 unless this tile completes the row
+            }
+            const bool mine = (sg != 0 || !cont0 || look) && !(skip_last && sg == nseg - 1);
+            if (mine && row < uint32_t(m)) y[row] = value;
         }
     }
 }
 
 // ----------------------------------------------------------------------------
-// Second and last launch of an SpMV: adds the carries (the global auxiliary
-// array of Section 4) and writes the zeros of empty rows.
+// Second launch of an SpMV, needed only when some tile starts more than LOOK
+// entries into a row: adds the carries (the global auxiliary array of Section 4).
 // One thread per tile, tiles in order across the lanes.  Tiles whose first row
 // is the same row R form a run (a row longer than a tile); a shuffle scan sums
 // the carries of a run and its last lane adds the total to y[R], which already
 // holds the part computed by the tile R starts in.  A run wholly inside one
 // wavefront is a plain read-modify-write (nobody else touches y[R] now); a run
 // cut by a wavefront boundary uses atomic adds, which commute.
-// Rows without nonzeros are stored by no tile; they get their 0 here when the
-// matrix has any (status bit set during conversion).
 // ----------------------------------------------------------------------------
 template <typename VT, typename IT>
 __global__ void __launch_bounds__(256)
@@ -909,13 +1039,7 @@ k_spmv_fixup(int m, int ntiles, const IT* __restrict__ row_ptr,
     VT cs = live ? carry[gid] : VT(0);
     const uint32_t r_after = (gid + 1 < ntiles) ? first_row(gid + 1) : 0xffffffffu;
     const uint32_t r_before = (t0 > 0 && t0 < ntiles) ? first_row(t0 - 1) : 0xffffffffu;
-    if (st & BAD_BITS) return;
-    if (st & CSR5_STATUS_HAS_EMPTY_ROWS) {
-        const int64_t stride = int64_t(gridDim.x) * blockDim.x;
-        for (int64_t r = gid; r < int64_t(m); r += stride)
-            if (row_ptr[r] == row_ptr[r + 1]) y[r] = VT(0);
-    }
-    if (t0 >= ntiles) return;
+    if ((st & BAD_BITS) || t0 >= ntiles) return;
 #pragma unroll
     for (int d = 1; d < OMEGA; d <<= 1) {
         VT up = __shfl_up(cs, d, OMEGA);
@@ -933,16 +1057,20 @@ k_spmv_fixup(int m, int ntiles, const IT* __restrict__ row_ptr,
     }
 }
 
-template <int SIGMA, typename VT, typename IT>
+template <int SIGMA, typename VT, typename IT, bool CAN_LOOK>
 hipError_t launch_spmv(const Geom& g, int m, int n, IT nnz, const IT* row_ptr,
                        const typename Index<IT>::tp_t* tile_ptr,
                        const uint32_t* tile_desc, const IT* eop, const int32_t* eo,
                        const int32_t* col_idx, const VT* val, const VT* x, VT* y,
-                       VT* carry, const uint32_t* status, hipStream_t s) {
+                       VT* carry, const uint32_t* status, const uint32_t* tile_head, const int32_t* last_col,
+                       const VT* last_val, bool zero_rows, hipStream_t s) {
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
     uint32_t nb_tiles = uint32_t((g.pc + WAVES - 1) / WAVES);
     uint32_t has_tail = (int64_t(g.pc) * g.T < nnz) ? 1u : 0u;
-    uint32_t nb = nb_tiles + has_tail;
+    // rows without nonzeros: up to 512 workgroups stride over the rows
+    size_t nb_zero = zero_rows ? (size_t(m) + WAVES * OMEGA - 1) / (WAVES * OMEGA) : 0;
+    if (nb_zero > 512) nb_zero = 512;
+    uint32_t nb = nb_tiles + has_tail + uint32_t(nb_zero);
     if (nb == 0) return hipSuccess;
     const size_t x_bytes = size_t(n) * sizeof(VT);
     uint32_t xcd_chunk = 0;                                        // contiguous eighths
@@ -950,20 +1078,20 @@ hipError_t launch_spmv(const Geom& g, int m, int n, IT nnz, const IT* row_ptr,
         xcd_chunk = (int64_t(nnz) / (m > 0 ? m : 1) <= g.T / Y_LINE_ROWS) ? 1u : XCD_CHUNK;
     else if (x_bytes < XCD_CONTIGUOUS_MIN_X_BYTES)                 // x at home in every L2
         xcd_chunk = XCD_CHUNK;
-    hipLaunchKernelGGL((k_spmv<SIGMA, VT, IT>), dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, nb_tiles, has_tail,
-                       xcd_chunk, row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status);
+    hipLaunchKernelGGL((k_spmv<SIGMA, VT, IT, CAN_LOOK>), dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, g.p, nb_tiles, has_tail,
+                       xcd_chunk, row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status, tile_head, last_col, last_val);
     return hipGetLastError();
 }
 
 template <int SIGMA, bool BACK, typename VT>
 hipError_t launch_transpose(const Geom& g, int n, int64_t nnz, int32_t* col_idx, VT* val,
-                            uint32_t* status, hipStream_t s) {
+                            uint32_t* status, int32_t* last_col, VT* last_val, hipStream_t s) {
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
     uint32_t nb = uint32_t((g.pc + WAVES - 1) / WAVES);
     if (nb == 0) nb = BACK ? 0 : 1;   // forward pass still validates the tail's columns
     if (nb == 0) return hipSuccess;
     hipLaunchKernelGGL((k_transpose<SIGMA, BACK, VT>), dim3(nb), dim3(WAVES * OMEGA), 0, s, g.pc, n, nnz,
-                       col_idx, val, status);
+                       col_idx, val, status, last_col, last_val);
     return hipGetLastError();
 }
 
@@ -1060,16 +1188,25 @@ struct csr5_handle_s {
     int32_t* eo;
     uint32_t* status;
     void* carry;           // one 8-byte slot per tile (incomplete one included): cross-tile sums of an SpMV
+    uint32_t* tile_head;   // per tile: entries of its first row that lie before it, saturated at LOOK + 1
+    // CSR-order copy of every complete tile's last LOOK entries (NULL for small sigma):
+    // two views of one array of LAST_REC_BYTES-byte records
+    int32_t* last_col;
+    void* last_val;
     void* owned;           // hipMalloc'ed block, or NULL when a workspace was given
     hipStream_t conv_stream;
     int device;            // HIP device that was current at conversion
     bool in_csr5_order;
+    // The device-side status word once the host has read it (-1 before): tells
+    // csr5_spmv* which launches this matrix needs.  Unknown means all of them.
+    std::atomic<int32_t> status_host;
 };
 
 namespace {
 
 struct Layout {
-    size_t off_tile_ptr, off_desc, off_eop, off_eo, off_carry, off_scan, off_status, total;
+    size_t off_tile_ptr, off_tile_head, off_desc, off_eop, off_eo, off_carry, off_last, off_scan, off_status, total;
+    bool has_last;
     size_t ndesc, eo_cap;
 };
 
@@ -1082,10 +1219,13 @@ Layout make_layout(int32_t m, const Geom& g, bool wide) {
     L.eo_cap = cap_a < cap_b ? cap_a : cap_b;
     size_t o = 0;
     L.off_tile_ptr = o; o += align256((size_t(g.p) + 1) * isz);
+    L.off_tile_head = o; o += align256((size_t(g.p) + 1) * 4);
     L.off_desc = o;     o += align256(L.ndesc * 4);
     L.off_eop = o;      o += align256((size_t(g.pc) + 1) * isz);
     L.off_eo = o;       o += align256(L.eo_cap * 4);
     L.off_carry = o;    o += align256((size_t(g.p) + 1) * 8);
+    L.has_last = g.sigma >= LOOK_MIN_SIGMA && g.pc > 0;
+    L.off_last = o;     o += L.has_last ? align256(size_t(g.pc) * LAST_REC_BYTES) : 0;
     L.off_scan = o;     o += align256((size_t(g.pc) / SCAN_CHUNK + 1) * isz);   // chunk totals of the scan
     L.off_status = o;   o += 256;
     L.total = o;
@@ -1194,6 +1334,9 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     h->eop = basep + L.off_eop;
     h->eo = reinterpret_cast<int32_t*>(basep + L.off_eo);
     h->carry = basep + L.off_carry;
+    h->tile_head = reinterpret_cast<uint32_t*>(basep + L.off_tile_head);
+    h->last_val = L.has_last ? basep + L.off_last : nullptr;                               // record + 0
+    h->last_col = L.has_last ? reinterpret_cast<int32_t*>(basep + L.off_last + LOOK * 8) : nullptr;
     h->status = reinterpret_cast<uint32_t*>(basep + L.off_status);
     h->conv_stream = s;
     if (hipGetDevice(&h->device) != hipSuccess) {
@@ -1202,6 +1345,7 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         return CSR5_EHIP;
     }
     h->in_csr5_order = true;
+    h->status_host.store(-1, std::memory_order_relaxed);
     {   // set-up time on this device: resolve the static scratch's address now, so
         // that csr5_spmv_static has nothing left to look up (failure is reported there)
         void* unused = nullptr;
@@ -1216,7 +1360,7 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         size_t nb = (work + 255) / 256;
         if (nb > 8192) nb = 8192;
         hipLaunchKernelGGL(k_tile_ptr<IT>, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p,
-                           tile_ptr, h->tile_desc, L.ndesc, h->status);
+                           tile_ptr, h->tile_head, h->tile_desc, L.ndesc, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && m > 0) {   // steps 2b + 3a
@@ -1251,7 +1395,8 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     }
     if (e == hipSuccess && nnz > 0) {   // step 4
         switch (sigma) {
-#define X(S) case S: e = launch_transpose<S, false, VT>(g, n, nnz, col_idx, val, h->status, s); break;
+#define X(S) case S: e = launch_transpose<S, false, VT>(g, n, nnz, col_idx, val, h->status, h->last_col,      \
+                                                        static_cast<VT*>(h->last_val), s); break;
             CSR5_FOR_SIGMA(X)
 #undef X
             default: e = hipErrorInvalidValue;
@@ -1325,25 +1470,33 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, in
     const IT* eop = static_cast<const IT*>(h->eop);
     hipError_t e = hipSuccess;
     VT* carry = static_cast<VT*>(carry_mem ? carry_mem : h->carry);
-    if (h->nnz > 0 && (which & LAUNCH_TILES)) {
+    // What the matrix needs beyond its tiles is known once the host has seen the
+    // status word of the conversion; until then everything is launched (the
+    // kernels look at the status word themselves and return at once if idle).
+    const int32_t known = h->status_host.load(std::memory_order_relaxed);
+    const bool zero_rows = known < 0 || (uint32_t(known) & CSR5_STATUS_HAS_EMPTY_ROWS);
+    const bool carries = known < 0 || (uint32_t(known) & STATUS_NEEDS_CARRY) || !h->last_col;
+    // the instantiation without the look-behind when the matrix is known not to use it
+    const bool can_look = h->last_col && (known < 0 || !(uint32_t(known) & STATUS_NEEDS_CARRY));
+    if (which & LAUNCH_TILES) {
+#define X(S) case S: e = (S >= LOOK_MIN_SIGMA && can_look)                                                          \
+        ? launch_spmv<S, VT, IT, (S >= LOOK_MIN_SIGMA)>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, \
+              eop, h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y, carry, h->status, h->tile_head,          \
+              h->last_col, static_cast<const VT*>(h->last_val), zero_rows, s)                                        \
+        : launch_spmv<S, VT, IT, false>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc,              \
+              eop, h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y, carry, h->status, h->tile_head,          \
+              h->last_col, static_cast<const VT*>(h->last_val), zero_rows, s);                                       \
+        break;
         switch (h->g.sigma) {
-#define X(S) case S: e = launch_spmv<S, VT, IT>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, eop, \
-                                                h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y,    \
-                                                carry, h->status, s); break;
             CSR5_FOR_SIGMA(X)
-#undef X
             default: e = hipErrorInvalidValue;
         }
+#undef X
     }
     if (e != hipSuccess) return CSR5_EHIP;
-    if (which & LAUNCH_FIXUP) {
-        // one thread per tile; when the matrix has empty rows the same grid strides over the rows
-        int ntiles = h->g.p;
+    if ((which & LAUNCH_FIXUP) && carries && h->g.p > 0) {
+        int ntiles = h->g.p;                                  // one thread per tile
         size_t nb = (size_t(ntiles) + 255) / 256;
-        size_t nb_rows = (size_t(h->m) + 255) / 256;
-        if (nb_rows > 512) nb_rows = 512;
-        if (nb < nb_rows) nb = nb_rows;
-        if (nb == 0) nb = 1;
         hipLaunchKernelGGL((k_spmv_fixup<VT, IT>), dim3(uint32_t(nb)), dim3(256), 0, s, h->m, ntiles, row_ptr,
                            tile_ptr, carry, y, h->status);
         if (hipGetLastError() != hipSuccess) return CSR5_EHIP;
@@ -1443,8 +1596,10 @@ int csr5_to_csr(csr5_handle_t h, void* hip_stream) {
     if (h->nnz > 0) {
         switch (h->g.sigma) {
 #define X(S) case S: e = (h->dtype == CSR5_DTYPE_F32)                                                            \
-        ? launch_transpose<S, true, float>(h->g, h->n, h->nnz, h->col_idx, static_cast<float*>(h->val), h->status, s)   \
-        : launch_transpose<S, true, double>(h->g, h->n, h->nnz, h->col_idx, static_cast<double*>(h->val), h->status, s); \
+        ? launch_transpose<S, true, float>(h->g, h->n, h->nnz, h->col_idx, static_cast<float*>(h->val), h->status,     \
+                                           nullptr, nullptr, s)                                                         \
+        : launch_transpose<S, true, double>(h->g, h->n, h->nnz, h->col_idx, static_cast<double*>(h->val), h->status,   \
+                                            nullptr, nullptr, s);                                                       \
         break;
             CSR5_FOR_SIGMA(X)
 #undef X
@@ -1468,6 +1623,7 @@ int csr5_status(csr5_handle_t h, uint32_t* status) {
     if (!h || !status) return CSR5_EINVAL;
     if (hipMemcpyAsync(status, h->status, 4, hipMemcpyDeviceToHost, h->conv_stream) != hipSuccess) return CSR5_EHIP;
     if (hipStreamSynchronize(h->conv_stream) != hipSuccess) return CSR5_EHIP;
+    h->status_host.store(int32_t(*status & 0x7fffffffu), std::memory_order_relaxed);
     *status &= STATUS_PUBLIC;
     return CSR5_OK;
 }

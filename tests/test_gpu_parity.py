@@ -427,3 +427,34 @@ def test_non_finite_x_stays_in_its_rows(sigma):
     inf_rows = ~fin & ~np.isnan(y_ref)
     assert np.array_equal(y[inf_rows], y_ref[inf_rows])        # same signed infinity
     B.csr5_free(h)
+
+
+@pytest.mark.parametrize("kind", ["short_rows", "long_rows", "empty_rows", "no_nonzeros"])
+def test_launch_set_before_and_after_status(kind):
+    """Which kernels an SpMV launches depends on what the host knows about the
+    matrix: everything until it has read the conversion's status word, only what
+    the matrix needs afterwards (no second kernel when no tile starts more than 32
+    entries into a row, no zero-filling workgroups without empty rows).  Both
+    must give the oracle's y."""
+    rng = np.random.default_rng(5)
+    if kind == "short_rows":          # every row is completed by the tile it ends in
+        a = wl.from_row_lengths(rng.integers(1, 33, size=6000), 5000, seed=1, name=kind)
+    elif kind == "long_rows":         # rows longer than several tiles: carries
+        lens = rng.integers(1, 30, size=3000)
+        lens[[7, 1500, 2999]] = [5000, 1300, 2100]
+        a = wl.from_row_lengths(lens, 9000, seed=2, name=kind)
+    elif kind == "empty_rows":
+        a = wl.from_row_lengths(rng.integers(0, 3, size=20000) * rng.integers(0, 30, size=20000), 7000, seed=3, name=kind)
+    else:
+        a = wl.from_row_lengths(np.zeros(1000, dtype=np.int64), 50, seed=4, name=kind)
+    for sigma in (4, 16, 37):
+        d = DeviceCsr(a)
+        ws = torch.empty(B.csr5_workspace_bytes(a.m, a.nnz, sigma), dtype=torch.uint8, device="cuda:0")
+        h = B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val, sigma=sigma, workspace=ws,
+                              flags=B.CSR5_FLAG_NO_HOST_CHECK)
+        say(kind, sigma, "nnz", a.nnz)
+        check_spmv(d, h, (kind, sigma, "status unknown"))
+        assert B.csr5_status(h) & 3 == 0
+        check_spmv(d, h, (kind, sigma, "status known"))
+        check_format(d, h, (kind, sigma))
+        B.csr5_free(h)
