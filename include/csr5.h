@@ -61,6 +61,11 @@ enum {
 #define CSR5_STATUS_HAS_DIRTY 4u   /* informational: some tile holds an empty row */
 #define CSR5_STATUS_HAS_EMPTY_ROWS 8u /* informational: the matrix has a row without nonzeros */
 
+/* ==========================================================================
+ * 1. The method: conversion (Section 3), SpMV (Section 4), back-conversion
+ *    (Section 3.6), release.
+ * ========================================================================== */
+
 /*
  * sigma from nnz/row (Section 3.2): the paper's four-way rule with bounds
  * <r, s, t, u> = <16, 16, 256, 16> measured on MI355X (nnz/row is the integer
@@ -93,7 +98,9 @@ size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma);
  *   row_ptr     int32[m+1], row_ptr[0] = 0, row_ptr[m] = nnz, non-decreasing.
  *               BORROWED: read now and again by every csr5_spmv (the format
  *               keeps it unchanged, Section 1); must outlive the handle.
- *   col_idx     int32[nnz], values in [0, n), 16-byte aligned.
+ *   col_idx     int32[nnz], values in [0, n).  Any int32-aligned address (a view into a
+ *               larger array is fine); a 16-byte aligned one lets the SpMV read it with
+ *               wider loads.
  *   val         double[nnz].
  *               Both MODIFIED IN PLACE: inside every complete tile the entries
  *               go from CSR order to tile column-major order (Section 3.1);
@@ -167,10 +174,24 @@ int csr5_spmv_ex(csr5_handle_t h, const double *x, double *y, void *hip_stream);
 int csr5_spmv_static(csr5_handle_t h, const double *x, double *y, void *hip_stream);
 
 /*
+ * CSR5 -> CSR (Section 3.6): transposes col_idx and val of every complete tile
+ * back to CSR order, in place.  The handle stays valid only for csr5_free.
+ */
+int csr5_to_csr(csr5_handle_t h, void *hip_stream);
+
+/* Releases the handle and whatever it allocated; never touches the caller's
+ * arrays or workspace.  NULL is accepted. */
+int csr5_free(csr5_handle_t h);
+
+/* ==========================================================================
+ * 2. Variants of the same calls: single precision, 64-bit indices.
+ * ========================================================================== */
+
+/*
  * Single-precision variant (the paper's Figure 3 is single precision): same
  * format, same kernels instantiated for float.  val, x and y are float arrays;
  * a handle made by csr5s_convert_ex is accepted by csr5s_spmv_ex,
- * csr5s_spmv_profile, csr5_to_csr and all the introspection calls, and refused
+ * csr5_to_csr and all the introspection calls (and csr5s_spmv_profile), and refused
  * (CSR5_EINVAL) by the double-precision SpMV calls, and vice versa.  Everything
  * said above about arguments, ownership and errors applies.
  */
@@ -178,8 +199,7 @@ int csr5s_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, 
                      float *val, int32_t sigma, void *workspace, size_t workspace_bytes,
                      void *hip_stream, uint32_t flags, csr5_handle_t *out);
 int csr5s_spmv_ex(csr5_handle_t h, const float *x, float *y, void *hip_stream);
-int csr5s_spmv_profile(csr5_handle_t h, const float *x, float *y, void *hip_stream, int reps,
-                       float *ms);
+
 
 /*
  * 64-bit index variant (Section 3.3 mentions it for tile_ptr: a 63-bit row
@@ -203,26 +223,10 @@ int csr5l_convert_ex(int32_t m, int32_t n, int64_t nnz, const int64_t *row_ptr, 
 int csr5l_get_arrays(csr5_handle_t h, const uint64_t **tile_ptr, const uint32_t **tile_desc,
                      const int64_t **empty_offset_ptr, const int32_t **empty_offset);
 
-/*
- * Measurement helper: launches each of the SpMV's two kernels `reps` times in a
- * row on the stream, HIP events before and after each series, waits, and returns
- * the mean duration per launch in milliseconds: ms[0] the tile kernel (all
- * complete tiles plus the workgroup for the incomplete one), ms[1] the carry
- * fix-up.  ms is a host array of 2 floats.  A full SpMV follows the two series,
- * so y ends up holding A*x as after csr5_spmv.
- */
-int csr5_spmv_profile(csr5_handle_t h, const double *x, double *y, void *hip_stream, int reps,
-                      float *ms);
-
-/*
- * CSR5 -> CSR (Section 3.6): transposes col_idx and val of every complete tile
- * back to CSR order, in place.  The handle stays valid only for csr5_free.
- */
-int csr5_to_csr(csr5_handle_t h, void *hip_stream);
-
-/* Releases the handle and whatever it allocated; never touches the caller's
- * arrays or workspace.  NULL is accepted. */
-int csr5_free(csr5_handle_t h);
+/* ==========================================================================
+ * 3. Introspection: the conversion's verdict on its input, the format's
+ *    geometry and arrays (what the parity tests compare).
+ * ========================================================================== */
 
 /*
  * Waits for the conversion's stream and returns the device-side status word
@@ -241,6 +245,9 @@ int csr5_status(csr5_handle_t h, uint32_t *status);
 int csr5_get_info(csr5_handle_t h, int32_t *omega, int32_t *sigma, int32_t *p, int32_t *p_complete,
                   int32_t *desc_words_per_lane, int32_t *empty_offset_len);
 
+/* m and n of the handle's matrix (host scalars, may be NULL). */
+int csr5_get_shape(csr5_handle_t h, int32_t *m, int32_t *n);
+
 /*
  * Device pointers to the handle's arrays (valid until csr5_free):
  *   tile_ptr          uint32[p+1]   bit 31 = tile holds an empty row (Section 3.3)
@@ -256,6 +263,38 @@ int csr5_get_arrays(csr5_handle_t h, const uint32_t **tile_ptr, const uint32_t *
                     const int32_t **empty_offset_ptr, const int32_t **empty_offset);
 
 /*
+ * Copies one of the handle's arrays to HOST memory (blocking; waits for the
+ * conversion's stream).  which: 0 tile_ptr, 1 tile_desc, 2 empty_offset_ptr,
+ * 3 empty_offset.  dst_host must hold `bytes` bytes; bytes must not exceed the
+ * array's size (empty_offset: 4*empty_offset_len), else CSR5_EINVAL.
+ */
+enum { CSR5_ARRAY_TILE_PTR = 0, CSR5_ARRAY_TILE_DESC = 1, CSR5_ARRAY_EMPTY_OFFSET_PTR = 2,
+       CSR5_ARRAY_EMPTY_OFFSET = 3 };
+int csr5_read_array(csr5_handle_t h, int which, void *dst_host, size_t bytes);
+
+/* Static description of an error code. */
+const char *csr5_strerror(int code);
+
+/* ==========================================================================
+ * 4. Measurement aids.  NOT part of the method: bench.py and the comparison of
+ *    Section 5.5 use them; nothing else in the library depends on them.
+ * ========================================================================== */
+
+/*
+ * Measurement helper: launches each of the SpMV's two kernels `reps` times in a
+ * row on the stream, HIP events before and after each series, waits, and returns
+ * the mean duration per launch in milliseconds: ms[0] the tile kernel (all
+ * complete tiles plus the workgroup for the incomplete one), ms[1] the carry
+ * fix-up (0 when this matrix does not need it).  ms is a host array of 2 floats.
+ * A full SpMV follows the two series, so y ends up holding A*x as after
+ * csr5_spmv.  csr5s_spmv_profile: the same for a single-precision handle.
+ */
+int csr5_spmv_profile(csr5_handle_t h, const double *x, double *y, void *hip_stream, int reps,
+                      float *ms);
+int csr5s_spmv_profile(csr5_handle_t h, const float *x, float *y, void *hip_stream, int reps,
+                       float *ms);
+
+/*
  * CSR row-block baselines on the plain CSR arrays (Section 2.2.1): CSR-scalar is
  * Algorithm 1 with one thread per row; CSR-vector reduces each row with
  * lanes_per_row lanes (2, 4, ..., 64; 0 = smallest power of two >= nnz/m).
@@ -268,19 +307,6 @@ int csr5_baseline_csr_scalar(int32_t m, const int32_t *row_ptr, const int32_t *c
 int csr5_baseline_csr_vector(int32_t m, int32_t nnz, const int32_t *row_ptr, const int32_t *col_idx,
                              const double *val, const double *x, double *y, int32_t lanes_per_row,
                              void *hip_stream);
-
-/*
- * Copies one of the handle's arrays to HOST memory (blocking; waits for the
- * conversion's stream).  which: 0 tile_ptr, 1 tile_desc, 2 empty_offset_ptr,
- * 3 empty_offset.  dst_host must hold `bytes` bytes; bytes must not exceed the
- * array's size (empty_offset: 4*empty_offset_len), else CSR5_EINVAL.
- */
-enum { CSR5_ARRAY_TILE_PTR = 0, CSR5_ARRAY_TILE_DESC = 1, CSR5_ARRAY_EMPTY_OFFSET_PTR = 2,
-       CSR5_ARRAY_EMPTY_OFFSET = 3 };
-int csr5_read_array(csr5_handle_t h, int which, void *dst_host, size_t bytes);
-
-/* Static description of an error code. */
-const char *csr5_strerror(int code);
 
 #ifdef __cplusplus
 }

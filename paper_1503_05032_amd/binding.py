@@ -30,7 +30,8 @@ CSR5_ARRAY_TILE_PTR, CSR5_ARRAY_TILE_DESC, CSR5_ARRAY_EMPTY_OFFSET_PTR, CSR5_ARR
 # every symbol include/csr5.h declares
 SYMBOLS = [
     "csr5_sigma_auto", "csr5_workspace_bytes", "csr5_convert", "csr5_convert_ex", "csr5_spmv",
-    "csr5_spmv_ex", "csr5_spmv_static", "csr5_spmv_profile", "csr5_to_csr", "csr5_free", "csr5_status", "csr5_get_info", "csr5_get_arrays",
+    "csr5_spmv_ex", "csr5_spmv_static", "csr5_spmv_profile", "csr5_to_csr", "csr5_free", "csr5_status", "csr5_get_info",
+    "csr5_get_shape", "csr5_get_arrays",
     "csr5_read_array", "csr5_strerror", "csr5_baseline_csr_scalar", "csr5_baseline_csr_vector",
     "csr5s_convert_ex", "csr5s_spmv_ex", "csr5s_spmv_profile",
     "csr5l_workspace_bytes", "csr5l_convert_ex", "csr5l_get_arrays",
@@ -94,6 +95,8 @@ def load():
     lib.csr5_status.argtypes = [vp, C.POINTER(u32)]
     lib.csr5_get_info.restype = C.c_int
     lib.csr5_get_info.argtypes = [vp] + [C.POINTER(i32)] * 6
+    lib.csr5_get_shape.restype = C.c_int
+    lib.csr5_get_shape.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
     lib.csr5_get_arrays.restype = C.c_int
     lib.csr5_get_arrays.argtypes = [vp] + [C.POINTER(vp)] * 4
     lib.csr5_read_array.restype = C.c_int
@@ -117,6 +120,27 @@ def _ptr(t):
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("expected a contiguous GPU tensor")
     return t.data_ptr() or None
+
+
+def _arr(t, dtypes, min_numel, name):
+    """Device address of a torch tensor after checking what the library cannot
+    check: element type and length.  A wrong one would make a kernel read or
+    write outside the tensor, so it is refused here, on the host.  Integers
+    (raw device addresses) and None pass through unchecked."""
+    if t is None or isinstance(t, int):
+        return _ptr(t)
+    import torch
+    names = {"i32": torch.int32, "i64": torch.int64, "f64": torch.float64, "f32": torch.float32, "u8": torch.uint8}
+    if t.dtype not in [names[d] for d in dtypes]:
+        raise ValueError(f"{name}: expected dtype {' or '.join(dtypes)}, got {t.dtype}")
+    if t.numel() < min_numel:
+        raise ValueError(f"{name}: needs at least {min_numel} elements, has {t.numel()}")
+    return _ptr(t)
+
+
+def _csr_args(m, n, nnz, row_ptr, col_idx, val, index, value):
+    return (_arr(row_ptr, [index], m + 1, "row_ptr"), _arr(col_idx, ["i32"], nnz, "col_idx"),
+            _arr(val, [value], nnz, "val"))
 
 
 def _stream(s):
@@ -149,7 +173,7 @@ def csr5_workspace_bytes(m, nnz, sigma=0):
 def csr5_convert(m, n, nnz, row_ptr, col_idx, val, check=True):
     """Returns the handle (an integer).  Uses the default stream and hipMalloc."""
     h = C.c_void_p()
-    rc = load().csr5_convert(m, n, nnz, _ptr(row_ptr), _ptr(col_idx), _ptr(val), C.byref(h))
+    rc = load().csr5_convert(m, n, nnz, *_csr_args(m, n, nnz, row_ptr, col_idx, val, "i32", "f64"), C.byref(h))
     _chk(rc, "csr5_convert", check)
     return h.value if check else (rc, h.value)
 
@@ -159,8 +183,8 @@ def csr5_convert_ex(m, n, nnz, row_ptr, col_idx, val, sigma=0, workspace=None, s
     """`workspace` is a torch uint8 GPU tensor (or None -> hipMalloc inside)."""
     h = C.c_void_p()
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    rc = load().csr5_convert_ex(m, n, nnz, _ptr(row_ptr), _ptr(col_idx), _ptr(val), int(sigma),
-                                _ptr(workspace), wsb, _stream(stream), int(flags), C.byref(h))
+    rc = load().csr5_convert_ex(m, n, nnz, *_csr_args(m, n, nnz, row_ptr, col_idx, val, "i32", "f64"), int(sigma),
+                                _arr(workspace, ["u8"], 0, "workspace"), wsb, _stream(stream), int(flags), C.byref(h))
     _chk(rc, "csr5_convert_ex", check)
     return h.value if check else (rc, h.value)
 
@@ -170,8 +194,8 @@ def csr5s_convert_ex(m, n, nnz, row_ptr, col_idx, val, sigma=0, workspace=None, 
     """Single precision: `val` is a float32 GPU tensor."""
     h = C.c_void_p()
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    rc = load().csr5s_convert_ex(m, n, nnz, _ptr(row_ptr), _ptr(col_idx), _ptr(val), int(sigma),
-                                 _ptr(workspace), wsb, _stream(stream), int(flags), C.byref(h))
+    rc = load().csr5s_convert_ex(m, n, nnz, *_csr_args(m, n, nnz, row_ptr, col_idx, val, "i32", "f32"), int(sigma),
+                                 _arr(workspace, ["u8"], 0, "workspace"), wsb, _stream(stream), int(flags), C.byref(h))
     _chk(rc, "csr5s_convert_ex", check)
     return h.value if check else (rc, h.value)
 
@@ -185,8 +209,8 @@ def csr5l_convert_ex(m, n, nnz, row_ptr, col_idx, val, sigma=0, workspace=None, 
     """64-bit index variant: `row_ptr` is an int64 GPU tensor, nnz may exceed 2^31."""
     h = C.c_void_p()
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    rc = load().csr5l_convert_ex(m, n, int(nnz), _ptr(row_ptr), _ptr(col_idx), _ptr(val), int(sigma),
-                                 _ptr(workspace), wsb, _stream(stream), int(flags), C.byref(h))
+    rc = load().csr5l_convert_ex(m, n, int(nnz), *_csr_args(m, n, nnz, row_ptr, col_idx, val, "i64", "f64"), int(sigma),
+                                 _arr(workspace, ["u8"], 0, "workspace"), wsb, _stream(stream), int(flags), C.byref(h))
     _chk(rc, "csr5l_convert_ex", check)
     return h.value if check else (rc, h.value)
 
@@ -200,34 +224,47 @@ def csr5l_get_arrays(h, check=True):
     return dict(zip(["tile_ptr", "tile_desc", "empty_offset_ptr", "empty_offset"], [a.value for a in v]))
 
 
+def _xy(h, x, y, value):
+    """x and y of an SpMV: element type of the entry point, at least n and m elements."""
+    m, n = csr5_get_shape(h) if h else (0, 0)
+    return _arr(x, [value], n, "x"), _arr(y, [value], m, "y")
+
+
+def csr5_get_shape(h):
+    """(m, n) of the handle's matrix."""
+    m, n = C.c_int32(), C.c_int32()
+    _chk(load().csr5_get_shape(h, C.byref(m), C.byref(n)), "csr5_get_shape", True)
+    return m.value, n.value
+
+
 def csr5s_spmv_ex(h, x, y, stream=None, check=True):
-    return _chk(load().csr5s_spmv_ex(h, _ptr(x), _ptr(y), _stream(stream)), "csr5s_spmv_ex", check)
+    return _chk(load().csr5s_spmv_ex(h, *_xy(h, x, y, "f32"), _stream(stream)), "csr5s_spmv_ex", check)
 
 
 def csr5s_spmv_profile(h, x, y, reps, stream=None):
     ms = (C.c_float * 2)()
-    _chk(load().csr5s_spmv_profile(h, _ptr(x), _ptr(y), _stream(stream), int(reps), ms),
+    _chk(load().csr5s_spmv_profile(h, *_xy(h, x, y, "f32"), _stream(stream), int(reps), ms),
          "csr5s_spmv_profile", True)
     return float(ms[0]), float(ms[1])
 
 
 def csr5_spmv(h, x, y, check=True):
-    return _chk(load().csr5_spmv(h, _ptr(x), _ptr(y)), "csr5_spmv", check)
+    return _chk(load().csr5_spmv(h, *_xy(h, x, y, "f64")), "csr5_spmv", check)
 
 
 def csr5_spmv_ex(h, x, y, stream=None, check=True):
-    return _chk(load().csr5_spmv_ex(h, _ptr(x), _ptr(y), _stream(stream)), "csr5_spmv_ex", check)
+    return _chk(load().csr5_spmv_ex(h, *_xy(h, x, y, "f64"), _stream(stream)), "csr5_spmv_ex", check)
 
 
 def csr5_spmv_static(h, x, y, stream=None, check=True):
     """csr5_spmv_ex without any allocation: the cross-tile array is the library's static one."""
-    return _chk(load().csr5_spmv_static(h, _ptr(x), _ptr(y), _stream(stream)), "csr5_spmv_static", check)
+    return _chk(load().csr5_spmv_static(h, *_xy(h, x, y, "f64"), _stream(stream)), "csr5_spmv_static", check)
 
 
 def csr5_spmv_profile(h, x, y, reps, stream=None):
     """Mean kernel durations in ms: (tile kernel, carry fix-up)."""
     ms = (C.c_float * 2)()
-    _chk(load().csr5_spmv_profile(h, _ptr(x), _ptr(y), _stream(stream), int(reps), ms),
+    _chk(load().csr5_spmv_profile(h, *_xy(h, x, y, "f64"), _stream(stream), int(reps), ms),
          "csr5_spmv_profile", True)
     return float(ms[0]), float(ms[1])
 
@@ -264,13 +301,16 @@ def csr5_get_arrays(h, check=True):
 
 
 def csr5_baseline_csr_scalar(m, row_ptr, col_idx, val, x, y, stream=None, check=True):
-    return _chk(load().csr5_baseline_csr_scalar(m, _ptr(row_ptr), _ptr(col_idx), _ptr(val), _ptr(x), _ptr(y),
+    nnz = 0
+    return _chk(load().csr5_baseline_csr_scalar(m, _arr(row_ptr, ["i32"], m + 1, "row_ptr"), _arr(col_idx, ["i32"], nnz, "col_idx"),
+                                                _arr(val, ["f64"], nnz, "val"), _arr(x, ["f64"], 0, "x"), _arr(y, ["f64"], m, "y"),
                                                 _stream(stream)), "csr5_baseline_csr_scalar", check)
 
 
 def csr5_baseline_csr_vector(m, nnz, row_ptr, col_idx, val, x, y, lanes_per_row=0, stream=None, check=True):
-    return _chk(load().csr5_baseline_csr_vector(m, nnz, _ptr(row_ptr), _ptr(col_idx), _ptr(val), _ptr(x),
-                                                _ptr(y), int(lanes_per_row), _stream(stream)),
+    return _chk(load().csr5_baseline_csr_vector(m, nnz, *_csr_args(m, 0, nnz, row_ptr, col_idx, val, "i32", "f64"),
+                                                _arr(x, ["f64"], 0, "x"), _arr(y, ["f64"], m, "y"),
+                                                int(lanes_per_row), _stream(stream)),
                 "csr5_baseline_csr_vector", check)
 
 

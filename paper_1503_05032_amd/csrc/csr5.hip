@@ -852,11 +852,26 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     constexpr int NC4 = (SIGMA + 3) / 4;                  // 16-byte col loads per lane
     typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
     i32x4 c4[NC4];
-    const i32x4* col4 = reinterpret_cast<const i32x4*>(col_idx + tile_base);
+    if ((reinterpret_cast<uintptr_t>(col_idx) & 15) == 0) {   // uniform
+        const i32x4* col4 = reinterpret_cast<const i32x4*>(col_idx + tile_base);
 #pragma unroll
-    for (int q = 0; q < NC4; q++) {
-        const int e4 = q * OMEGA + lane;                  // index of the int4 inside the tile
-        c4[q] = (SIGMA % 4 == 0 || e4 < T / 4) ? __builtin_nontemporal_load(&col4[e4]) : i32x4{0, 0, 0, 0};
+        for (int q = 0; q < NC4; q++) {
+            const int e4 = q * OMEGA + lane;              // index of the int4 inside the tile
+            c4[q] = (SIGMA % 4 == 0 || e4 < T / 4) ? __builtin_nontemporal_load(&col4[e4]) : i32x4{0, 0, 0, 0};
+        }
+    } else {      // col_idx is a view at an odd offset into a caller's array: the same four entries, one by one
+        const int32_t* col1 = col_idx + tile_base;
+#pragma unroll
+        for (int q = 0; q < NC4; q++) {
+            const int e4 = q * OMEGA + lane;
+            c4[q] = i32x4{0, 0, 0, 0};
+            if (SIGMA % 4 == 0 || e4 < T / 4) {
+                c4[q].x = __builtin_nontemporal_load(&col1[4 * e4 + 0]);
+                c4[q].y = __builtin_nontemporal_load(&col1[4 * e4 + 1]);
+                c4[q].z = __builtin_nontemporal_load(&col1[4 * e4 + 2]);
+                c4[q].w = __builtin_nontemporal_load(&col1[4 * e4 + 3]);
+            }
+        }
     }
     VT v[SIGMA];
 #pragma unroll
@@ -1295,8 +1310,9 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     if (m < 0 || n < 0 || nnz < 0) return CSR5_EINVAL;
     if (!row_ptr) return CSR5_EINVAL;                      // row_ptr has m+1 >= 1 entries
     if (nnz > 0 && (!col_idx || !val || m == 0 || n == 0)) return CSR5_EINVAL;
-    // the kernels read col_idx with 16-byte accesses and val element-wise
-    if ((reinterpret_cast<uintptr_t>(col_idx) & 15) || (reinterpret_cast<uintptr_t>(val) & (sizeof(VT) - 1)) ||
+    // natural alignment of every element is all the kernels need (the SpMV reads
+    // col_idx sixteen bytes at a time when its base allows that, else four)
+    if ((reinterpret_cast<uintptr_t>(col_idx) & 3) || (reinterpret_cast<uintptr_t>(val) & (sizeof(VT) - 1)) ||
         (reinterpret_cast<uintptr_t>(row_ptr) & (sizeof(IT) - 1))) return CSR5_EINVAL;
     if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
     if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX) return CSR5_ERANGE;
@@ -1645,6 +1661,13 @@ int csr5_get_info(csr5_handle_t h, int32_t* omega, int32_t* sigma, int32_t* p, i
         if (v < 0 || v > INT32_MAX) return CSR5_ERANGE;
         *empty_offset_len = int32_t(v);
     }
+    return CSR5_OK;
+}
+
+int csr5_get_shape(csr5_handle_t h, int32_t* m, int32_t* n) {
+    if (!h) return CSR5_EINVAL;
+    if (m) *m = h->m;
+    if (n) *n = h->n;
     return CSR5_OK;
 }
 

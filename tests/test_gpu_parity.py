@@ -360,8 +360,11 @@ def _run32(a, sigma):
     bad = np.nonzero(~(np.abs(got - y_ref) <= TOL32 * s + 1e-30))[0]
     assert bad.size == 0, (a.name, sigma, int(bad.size), int(bad[0]), got[bad[0]], y_ref[bad[0]], s[bad[0]])
     assert np.all(got[np.diff(a.row_ptr) == 0] == 0.0)
-    # the double-precision calls refuse a single-precision handle
-    assert B.csr5_spmv_ex(h, x, y, check=False) == B.CSR5_EINVAL
+    # the double-precision calls refuse a single-precision handle: the binding by the
+    # tensors' type, the library (given raw addresses) by the handle's
+    with pytest.raises(ValueError):
+        B.csr5_spmv_ex(h, x, y, check=False)
+    assert B.csr5_spmv_ex(h, x.data_ptr(), y.data_ptr(), check=False) == B.CSR5_EINVAL
     B.csr5_to_csr(h)
     torch.cuda.synchronize()
     if a.nnz:
@@ -379,7 +382,7 @@ def test_single_precision_edge_cases(sigma):
         _run32(a, sigma)
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_single_precision_full_size(cfg):
     a = wl.config(cfg)
     say("f32", a.stats())
@@ -458,3 +461,139 @@ def test_launch_set_before_and_after_status(kind):
         check_spmv(d, h, (kind, sigma, "status known"))
         check_format(d, h, (kind, sigma))
         B.csr5_free(h)
+
+
+
+def test_no_rows_and_no_columns():
+    """m = 0 is a valid matrix (CSR5_OK, nothing to compute); so is a matrix
+    without columns, which can hold no nonzero."""
+    dev = torch.device("cuda:0")
+    rp0 = torch.zeros(1, dtype=torch.int32, device=dev)
+    dummy_c = torch.zeros(4, dtype=torch.int32, device=dev)
+    dummy_v = torch.zeros(8, dtype=torch.float64, device=dev)
+    y = torch.full((4,), 5.0, dtype=torch.float64, device=dev)
+    for ws_on in (False, True):
+        ws = None
+        if ws_on:
+            ws = torch.empty(B.csr5_workspace_bytes(0, 0, 0), dtype=torch.uint8, device=dev)
+        h = B.csr5_convert_ex(0, 7, 0, rp0, dummy_c, dummy_v, workspace=ws)          # m = 0, n > 0
+        info = B.csr5_get_info(h)
+        assert info["p"] == 0 and info["p_complete"] == 0 and info["empty_offset_len"] == 0
+        assert B.csr5_status(h) & 3 == 0
+        assert B.csr5_spmv_ex(h, dummy_v, y) == B.CSR5_OK
+        assert B.csr5_spmv_static(h, dummy_v, y) == B.CSR5_OK
+        torch.cuda.synchronize()
+        assert np.all(y.cpu().numpy() == 5.0)                 # no row: nothing written
+        assert B.csr5_to_csr(h) == B.CSR5_OK
+        B.csr5_free(h)
+    h = B.csr5_convert(0, 0, 0, rp0, None, None)              # m = n = nnz = 0 through the plain entry point
+    assert B.csr5_spmv(h, None, None) == B.CSR5_OK
+    B.csr5_free(h)
+    # n = 0 and nnz = 0 with rows: every row is empty, y = 0
+    a = wl.from_row_lengths(np.zeros(777, dtype=np.int64), 0, seed=1, name="no_columns")
+    assert a.n == 0 and a.nnz == 0
+    d = DeviceCsr(a)
+    for use_ws in (True, False):
+        h = convert(d, use_workspace=use_ws)
+        check_format(d, h, "no columns")
+        check_spmv(d, h, "no columns")
+        assert np.all(d.y.cpu().numpy()[:a.m] == 0.0)
+        B.csr5_free(h)
+    # nnz > 0 needs rows and columns
+    rc, h = B.csr5_convert_ex(0, 5, 3, rp0, dummy_c, dummy_v, check=False)
+    assert rc == B.CSR5_EINVAL and not h
+    rp6 = torch.tensor([0, 1, 2, 3, 3, 3], dtype=torch.int32, device=dev)
+    rc, h = B.csr5_convert_ex(5, 0, 3, rp6, dummy_c, dummy_v, check=False)
+    assert rc == B.CSR5_EINVAL and not h
+
+
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_plain_convert_on_full_size_irregular(cfg):
+    """csr5_convert (blocking, hipMalloc inside, automatic sigma, default stream) on
+    a full-size irregular configuration."""
+    a = wl.config(cfg)
+    d = DeviceCsr(a)
+    h = B.csr5_convert(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val)
+    say("config", cfg, B.csr5_get_info(h))
+    check_format(d, h, f"plain convert config{cfg}")
+    check_spmv(d, h, f"plain convert config{cfg}")
+    B.csr5_free(h)
+
+
+@pytest.mark.parametrize("offset", [1, 2, 3])
+def test_col_idx_view_at_an_odd_offset(offset):
+    """col_idx and val may be views into larger arrays: a col_idx base that is
+    only 4-byte aligned is read entry by entry instead of sixteen bytes at a time."""
+    for a, sigma in ((wl.config(4, scale=0.02), 16), (wl.tiny_uniform(m=900, n=700, seed=3), 5),
+                     (wl.config(2, scale=0.01), 0)):
+        d = DeviceCsr(a)
+        big_c = torch.full((a.nnz + 8,), -7, dtype=torch.int32, device="cuda:0")
+        big_v = torch.full((a.nnz + 8,), float("nan"), dtype=torch.float64, device="cuda:0")
+        assert big_c.data_ptr() % 16 == 0
+        big_c[offset:offset + a.nnz] = d.col_idx
+        big_v[offset:offset + a.nnz] = d.val
+        d.col_idx = big_c[offset:offset + a.nnz]
+        d.val = big_v[offset:offset + a.nnz]
+        assert d.col_idx.data_ptr() % 16 == 4 * offset
+        h = convert(d, sigma=sigma)
+        say("offset", offset, a.name, B.csr5_get_info(h)["sigma"])
+        check_format(d, h, ("offset view", offset))
+        check_spmv(d, h, ("offset view", offset))
+        B.csr5_to_csr(h)
+        torch.cuda.synchronize()
+        assert np.array_equal(d.col_idx.cpu().numpy(), a.col_idx) and np.array_equal(d.val.cpu().numpy(), a.val)
+        # nothing outside the view was touched
+        assert int((big_c[:offset] != -7).sum()) == 0 and int((big_c[offset + a.nnz:] != -7).sum()) == 0
+        assert bool(torch.isnan(big_v[:offset]).all()) and bool(torch.isnan(big_v[offset + a.nnz:]).all())
+        B.csr5_free(h)
+
+
+def test_two_handles_on_two_streams():
+    """Two matrices, two handles, SpMVs of both in flight at the same time on two
+    streams (every handle has its own auxiliary array): both results are the
+    oracle's, whatever the interleaving."""
+    a1, a2 = wl.config(3, scale=0.05), wl.config(4, scale=0.05)
+    d1, d2 = DeviceCsr(a1), DeviceCsr(a2)
+    h1, h2 = convert(d1, sigma=0), convert(d2, sigma=8)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    ys1 = [torch.full_like(d1.y, float("nan")) for _ in range(6)]
+    ys2 = [torch.full_like(d2.y, float("nan")) for _ in range(6)]
+    for k in range(6):                       # enqueue alternately, no waiting in between
+        B.csr5_spmv_ex(h1, d1.x, ys1[k], stream=s1)
+        B.csr5_spmv_ex(h2, d2.x, ys2[k], stream=s2)
+    s1.synchronize()
+    s2.synchronize()
+    for k in range(6):
+        _check_y(ys1[k].cpu().numpy()[:a1.m], a1, ("stream 1", k))
+        _check_y(ys2[k].cpu().numpy()[:a2.m], a2, ("stream 2", k))
+    B.csr5_free(h1)
+    B.csr5_free(h2)
+
+
+
+def test_binding_refuses_wrong_types_and_short_arrays():
+    """A tensor of the wrong element type or length would make a kernel leave its
+    array; the binding refuses it on the host before anything is launched."""
+    a = wl.tiny_uniform(m=300, n=200, seed=2)
+    d = DeviceCsr(a)
+    with pytest.raises(ValueError):
+        B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr.long(), d.col_idx, d.val)          # int64 row_ptr
+    with pytest.raises(ValueError):
+        B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val.float())         # float32 val
+    with pytest.raises(ValueError):
+        B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr[:-1], d.col_idx, d.val)            # short row_ptr
+    with pytest.raises(ValueError):
+        B.csr5_convert_ex(a.m, a.n, a.nnz, d.row_ptr, d.col_idx[:-1], d.val)            # short col_idx
+    with pytest.raises(ValueError):
+        B.csr5l_convert_ex(a.m, a.n, a.nnz, d.row_ptr, d.col_idx, d.val)                # int32 row_ptr, wide entry point
+    h = convert(d, sigma=4)
+    assert B.csr5_get_shape(h) == (a.m, a.n)
+    with pytest.raises(ValueError):
+        B.csr5_spmv_ex(h, d.x[:-1], d.y)                                                # short x
+    with pytest.raises(ValueError):
+        B.csr5_spmv_ex(h, d.x, d.y[:a.m - 1])                                           # short y
+    with pytest.raises(ValueError):
+        B.csr5_spmv_ex(h, d.x.float(), d.y)
+    check_spmv(d, h, "after refusals")
+    B.csr5_free(h)

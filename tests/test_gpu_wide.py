@@ -41,7 +41,7 @@ def test_wide_edge_cases(sigma):
         B.csr5_free(h)
 
 
-@pytest.mark.parametrize("cfg", [1, 3, 4])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_wide_full_size_configs(cfg):
     a = wl.config(cfg)
     say("wide", a.stats())
