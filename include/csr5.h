@@ -70,7 +70,7 @@ enum {
  * sigma from nnz/row (Section 3.2): the paper's four-way rule with bounds
  * <r, s, t, u> = <16, 16, 256, 16> measured on MI355X (nnz/row is the integer
  * quotient nnz/m; on this GPU the best sigma turned out not to depend on it).
- * One addition: when nnz/row <= t and the matrix would have fewer than 16384
+ * One addition: when nnz/row <= t and the matrix would have fewer than 12288
  * tiles at that sigma, sigma = 8 (a small matrix needs the parallelism more than
  * the amortisation).  Pure host arithmetic.
  */
@@ -83,7 +83,7 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * (p_c*W*64 words) + empty_offset_ptr (p_c+1 words) + empty_offset (at most
  * min(m + p_c, p_c*T) words) + the SpMV's auxiliary array (p+1 doubles) + one
  * word per tile saying how far into its first row the tile starts (p+1) + for
- * sigma >= 8 a copy of every complete tile's last 32 (col_idx, val) pairs in CSR
+ * 8 <= sigma <= 32 a copy of every complete tile's last 32 (col_idx, val) pairs in CSR
  * order (384 bytes per tile; it lets a tile finish a row that began in the
  * previous tile without a second kernel) + the conversion's scan scratch
  * (p_c/8192 + 1 words) + a status word, each rounded up to 256 bytes.
@@ -137,7 +137,7 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, i
  * complete tile by a row-wise SIMD reduction).  A tile's first segment, when it
  * continues a row of an earlier tile, is completed in one of two ways, fixed per
  * matrix at conversion: if no tile starts more than 32 entries into a row
- * (sigma >= 8), every tile re-reads the head of its first row and stores the
+ * (and 8 <= sigma <= 32), every tile re-reads the head of its first row and stores the
  * finished row, and the SpMV is ONE kernel; otherwise those segments go through
  * an auxiliary array that a second small kernel adds to y (Section 4's "global
  * auxiliary array").  Which of the two, and whether rows without nonzeros need

@@ -10,7 +10,9 @@ sigma, the time at the library's automatic sigma and the loss against the best.
 The probe matrices have fixed row lengths 1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 64,
 128, 256, 512, 2048 (banded random columns), which is what the rule is a function
 of, at about 8 M nonzeros ("probes": fewer tiles than the chip holds wavefronts
-for) and, for a few lengths, at about 60 M ("bigprobes").
+for) and, for a few lengths, at about 60 M ("bigprobes"); "sizeprobes" are rows of
+8 and 27 entries at 8 to 40 M nonzeros, for the size below which the smaller
+tile wins.
 Needs a GPU.  Results are facts about the machine, not parity items.
 """
 from __future__ import annotations
@@ -69,6 +71,7 @@ def sweep(a, sigmas, reps=100):
         ws = torch.empty(B.csr5_workspace_bytes(a.m, a.nnz, sg), dtype=torch.uint8, device=dev)
         h = B.csr5_convert_ex(a.m, a.n, a.nnz, row_ptr, col, val, sigma=sg, workspace=ws,
                               flags=B.CSR5_FLAG_NO_HOST_CHECK)
+        assert B.csr5_status(h) & 3 == 0          # the handle learns which launches the matrix needs
         out[sg] = time_spmv(B, torch, h, x, y, reps)
         B.csr5_free(h)
         del col, val, ws
@@ -95,6 +98,12 @@ def main():
     for tok in args.workloads.split(","):
         if tok == "probes":
             mats += [probe_matrix(L) for L in (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 64, 128, 256, 512, 2048)]
+        elif tok == "sizeprobes":      # where the small-matrix rule (sigma 8 below 12288 tiles) should end
+            for L in (8, 27):
+                for mn in (8, 12, 16, 20, 24, 30, 40):
+                    a = probe_matrix(L, nnz_target=mn * 1_000_000)
+                    a.name = f"size{mn}M_" + a.name
+                    mats.append(a)
         elif tok == "bigprobes":
             for L in (1, 2, 4, 8, 12, 32, 128):
                 a = probe_matrix(L, nnz_target=60_000_000)

@@ -35,9 +35,11 @@ constexpr uint32_t STATUS_NEEDS_CARRY = 1u << 17;
 // three cache lines per tile, read by every tile without first asking how long
 // its head is (a dependent load at that point costs more than the lines); 384
 // bytes per tile, not kept for sigma < LOOK_MIN_SIGMA, where it would be a large
-// part of the matrix (those matrices always take the auxiliary-array path).
+// part of the matrix, nor for sigma > LOOK_MAX_SIGMA, where the tile kernel has
+// no registers to spare (those matrices always take the auxiliary-array path).
 constexpr int LOOK = 32;
-constexpr int LOOK_MIN_SIGMA = 8;
+constexpr int LOOK_MIN_SIGMA = 8, LOOK_MAX_SIGMA = 32;
+constexpr bool look_sigma(int sigma) { return sigma >= LOOK_MIN_SIGMA && sigma <= LOOK_MAX_SIGMA; }
 // One record per tile: LOOK values (8 bytes each, 4 used in single precision)
 // followed by LOOK column indices, contiguous, so that a tile fetches it with one
 // run of three cache lines.  Strides of the two views of the record array:
@@ -53,9 +55,12 @@ constexpr int NUM_XCD = 8;  // MI355X: 8 accelerator dies, each with its own L2
 // (16 wins by 2-3 % from 1 to 256 nonzeros per row), so r = s = u.
 constexpr int RULE_R = 16, RULE_S = 16, RULE_T = 256, RULE_U = 16;
 // What does matter is the number of tiles: the chip holds 256 CUs x 16
-// wavefronts of this kernel, and below about four rounds of them the ramp-up and
-// the last partial round dominate; such a matrix gets the smaller tile.
-constexpr int64_t RULE_MIN_TILES = 4 * 256 * 16;
+// wavefronts of this kernel, and below about three rounds of them the ramp-up and
+// the last partial round dominate; such a matrix gets the smaller tile.  Placed
+// with matrices of 8 and of 27 entries per row at 8 to 40 M nonzeros: at sigma 16
+// the 27-per-row ones win from 12 M nonzeros on (7 % at 14 M), the 8-per-row
+// ones are within 2 % either way between 12 M and 20 M.
+constexpr int64_t RULE_MIN_TILES = 3 * 256 * 16;
 constexpr int RULE_SIGMA_SMALL = 8;
 
 // Index width of row_ptr, tile_ptr and empty_offset_ptr.  int32 is the layout the
@@ -946,15 +951,24 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
             c[k] = cb[(e / SIGMA) * PITCH + (e % SIGMA)];
         }
         wave_sync_lds();
-#pragma unroll
-        for (int k = 0; k < SIGMA; k++) xv[k] = x[c[k]];
+        // All gathers of the tile are in flight together up to sigma = 32.  Beyond
+        // that they go in groups of 16 (8 from sigma = 47 on): each gather holds four registers (address and
+        // result) next to the tile's 2*sigma value registers, and with all of them
+        // at once the kernel ran out of the 256 a wavefront can have (sigma >= 42:
+        // spills into accumulator registers, one wavefront per SIMD).
+        constexpr int GROUP = SIGMA > 46 ? 8 : (SIGMA > 32 ? 16 : SIGMA);
         if constexpr (CAN_LOOK) head_x = x[head_c];
 #pragma unroll
-        for (int k = 0; k < SIGMA; k++) {
-            const int e = k * OMEGA + lane;
-            xb[(e / SIGMA) * PITCH + (e % SIGMA)] = xv[k];
+        for (int k0 = 0; k0 < SIGMA; k0 += GROUP) {
+#pragma unroll
+            for (int k = k0; k < k0 + GROUP && k < SIGMA; k++) xv[k] = x[c[k]];
+#pragma unroll
+            for (int k = k0; k < k0 + GROUP && k < SIGMA; k++) {
+                const int e = k * OMEGA + lane;
+                xb[(e / SIGMA) * PITCH + (e % SIGMA)] = xv[k];
+            }
+            wave_sync_lds();
         }
-        wave_sync_lds();
 #pragma unroll
         for (int j = 0; j < SIGMA; j++) xv[j] = xb[lane * PITCH + j];
         wave_sync_lds();
@@ -1239,7 +1253,7 @@ Layout make_layout(int32_t m, const Geom& g, bool wide) {
     L.off_eop = o;      o += align256((size_t(g.pc) + 1) * isz);
     L.off_eo = o;       o += align256(L.eo_cap * 4);
     L.off_carry = o;    o += align256((size_t(g.p) + 1) * 8);
-    L.has_last = g.sigma >= LOOK_MIN_SIGMA && g.pc > 0;
+    L.has_last = look_sigma(g.sigma) && g.pc > 0;
     L.off_last = o;     o += L.has_last ? align256(size_t(g.pc) * LAST_REC_BYTES) : 0;
     L.off_scan = o;     o += align256((size_t(g.pc) / SCAN_CHUNK + 1) * isz);   // chunk totals of the scan
     L.off_status = o;   o += 256;
@@ -1495,8 +1509,8 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, in
     // the instantiation without the look-behind when the matrix is known not to use it
     const bool can_look = h->last_col && (known < 0 || !(uint32_t(known) & STATUS_NEEDS_CARRY));
     if (which & LAUNCH_TILES) {
-#define X(S) case S: e = (S >= LOOK_MIN_SIGMA && can_look)                                                          \
-        ? launch_spmv<S, VT, IT, (S >= LOOK_MIN_SIGMA)>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, \
+#define X(S) case S: e = (look_sigma(S) && can_look)                                                                \
+        ? launch_spmv<S, VT, IT, look_sigma(S)>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, \
               eop, h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y, carry, h->status, h->tile_head,          \
               h->last_col, static_cast<const VT*>(h->last_val), zero_rows, s)                                        \
         : launch_spmv<S, VT, IT, false>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc,              \

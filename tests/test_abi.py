@@ -42,9 +42,9 @@ def test_sigma_rule_matches_paper_shape(lib):
         assert vals[q - 1] == oracle.sigma_rule(q * m, m, r, s, t, u), q
     assert B.csr5_sigma_auto(0, 0) == r
     assert all(B.CSR5_SIGMA_MIN <= v <= B.CSR5_SIGMA_MAX for v in vals)
-    # small-matrix clamp: fewer than 16384 tiles  ->  sigma 8  (only up to t nonzeros per row)
+    # small-matrix clamp: fewer than 12288 tiles  ->  sigma 8  (only up to t nonzeros per row)
     assert B.csr5_sigma_auto(12 * 1000, 1000) == 8
-    big = 16384 * 64 * r
+    big = 12288 * 64 * r
     assert B.csr5_sigma_auto(big, big // 12) == r
     assert B.csr5_sigma_auto(big - 1, big // 12) == 8
     assert B.csr5_sigma_auto(1000 * 1000, 1000) == u
