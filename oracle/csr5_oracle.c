@@ -146,56 +146,42 @@ void oracle_bit_flag(int32_t m, int32_t nnz, const int32_t *row_ptr,
     free(flat);
 }
 
-/* Algorithm 2: serial segmented sum on integers (used by Algorithm 5). */
-static void segmented_sum_i32(int32_t *in, const uint8_t *flag, int32_t length)
-{
-    for (int32_t i = 0; i < length; i++) {
-        if (flag[i]) {
-            int32_t j = i + 1;
-            while (j < length && !flag[j]) {
-                in[i] = in[i] + in[j];
-                j = j + 1;
-            }
-        } else {
-            in[i] = 0;
-        }
-    }
-}
-
 /* ------------------------------------------------------------------ */
-/* Algorithm 5 (Section 3.4): y_offset and seg_offset of every complete */
-/* tile.  y_offset = exclusive prefix sum of the per-column flag counts */
-/* (the forced first flag counts); seg_offset = segmented sum of        */
-/* (1 - tmp_bit) with tmp_bit as head flags, hence 0 for a column with  */
-/* no TRUE flag.  Outputs are [pc][omega] int32.                        */
+/* y_offset and seg_offset of every complete tile, from what Section    */
+/* 3.4 says they mean (Algorithm 5 computes the same two arrays with a  */
+/* prefix sum and a segmented sum):                                     */
+/*   y_offset[i]   = number of TRUE flags in the tile's columns before  */
+/*                   column i (the forced first flag counts): the       */
+/*                   segment, counted from the tile's first row, that   */
+/*                   the first flag of column i opens;                  */
+/*   seg_offset[i] = for a column that holds a TRUE flag, how many      */
+/*                   columns directly to its right hold none (their     */
+/*                   partial sums belong to this column's last          */
+/*                   segment); 0 for a column without a flag.           */
+/* Outputs are [pc][omega] int32.                                       */
 /* ------------------------------------------------------------------ */
 void oracle_y_seg_offset(int64_t pc, int32_t omega, int32_t sigma, const uint8_t *bit_flag,
                          int32_t *y_offset, int32_t *seg_offset)
 {
-    uint8_t *tmp_bit = (uint8_t *)malloc((size_t)omega);
+    uint8_t *has_flag = (uint8_t *)malloc((size_t)omega);
     for (int64_t tid = 0; tid < pc; tid++) {
-        const uint8_t *bf = bit_flag + tid * omega * sigma;
-        int32_t *yo = y_offset + tid * omega;
-        int32_t *so = seg_offset + tid * omega;
-        memset(tmp_bit, 0, (size_t)omega);
-        for (int32_t i = 0; i < omega; i++) {
-            yo[i] = 0;
-            for (int32_t j = 0; j < sigma; j++) {
-                yo[i] = yo[i] + bf[i * sigma + j];
-                tmp_bit[i] = tmp_bit[i] | bf[i * sigma + j];
-            }
-            so[i] = 1 - tmp_bit[i];
+        const uint8_t *tile_flags = bit_flag + tid * omega * sigma;
+        int32_t flags_before = 0;
+        for (int32_t col = 0; col < omega; col++) {
+            int32_t here = 0;
+            for (int32_t j = 0; j < sigma; j++) here += tile_flags[col * sigma + j];
+            y_offset[tid * omega + col] = flags_before;
+            flags_before += here;
+            has_flag[col] = (uint8_t)(here > 0);
         }
-        /* exclusive prefix sum */
-        int32_t run = 0;
-        for (int32_t i = 0; i < omega; i++) {
-            int32_t c = yo[i];
-            yo[i] = run;
-            run += c;
+        for (int32_t col = 0; col < omega; col++) {
+            int32_t empty_to_the_right = 0;
+            if (has_flag[col])
+                for (int32_t nb = col + 1; nb < omega && !has_flag[nb]; nb++) empty_to_the_right++;
+            seg_offset[tid * omega + col] = empty_to_the_right;
         }
-        segmented_sum_i32(so, tmp_bit, omega);
     }
-    free(tmp_bit);
+    free(has_flag);
 }
 
 /* ceil(log2(v)) for v >= 1 */
@@ -254,12 +240,16 @@ void oracle_pack_desc(int64_t pc, int32_t omega, int32_t sigma, const uint8_t *b
 }
 
 /* ------------------------------------------------------------------ */
-/* Algorithm 7 (Section 3.4): empty_offset.  One entry per TRUE flag of */
-/* every flagged ("dirty") complete tile, flags visited column by       */
-/* column (= CSR order): row that owns the flagged nonzero, relative to */
-/* the tile's first row.  The per-tile arrays are concatenated;         */
+/* empty_offset (Section 3.4; Algorithm 7 builds the same array with a  */
+/* binary search per flag).  In a tile that holds an empty row, segment */
+/* number s no longer is row tile_ptr + s, so the format stores, for    */
+/* every TRUE flag of such a tile in CSR order, which row the flagged   */
+/* nonzero belongs to, relative to the tile's first row.  The owner of  */
+/* nonzero q is the row r with row_ptr[r] <= q < row_ptr[r+1]; flags    */
+/* are visited in increasing q, so one row cursor that only moves       */
+/* forward finds them all.  The per-tile arrays are concatenated;       */
 /* empty_offset_ptr[tid] (exclusive prefix sum of the per-tile lengths, */
-/* 0 for tiles that are not dirty, int32[pc+1]) says where tile tid's   */
+/* 0 for tiles without an empty row, int32[pc+1]) says where tile tid's */
 /* entries start -- the paper does not say how they are laid out.       */
 /* Call with empty_offset == NULL to get only empty_offset_ptr.         */
 /* ------------------------------------------------------------------ */
@@ -269,29 +259,23 @@ void oracle_empty_offset(int32_t m, int32_t nnz, const int32_t *row_ptr, int32_t
 {
     int64_t T = (int64_t)omega * sigma;
     int64_t pc = oracle_num_complete_tiles(nnz, omega, sigma);
-    int32_t run = 0;
+    int32_t written = 0;
+    int32_t owner = 0;                         /* row cursor, never moves back */
+    (void)m;
     for (int64_t tid = 0; tid < pc; tid++) {
-        empty_offset_ptr[tid] = run;
+        empty_offset_ptr[tid] = written;
         if (!(tile_ptr[tid] & DIRTY)) continue;
-        int32_t length = 0;
-        for (int64_t k = 0; k < T; k++) length += bit_flag[tid * T + k];
-        if (empty_offset) {
-            int32_t eid = 0;
-            for (int32_t i = 0; i < omega; i++) {
-                for (int32_t j = 0; j < sigma; j++) {
-                    if (bit_flag[(tid * omega + i) * sigma + j]) {
-                        int64_t ptr = tid * T + (int64_t)i * sigma + j;
-                        int64_t idx = count_le(row_ptr, m, ptr) - 1;
-                        idx = idx - (int64_t)(tile_ptr[tid] & ~DIRTY);
-                        empty_offset[run + eid] = (int32_t)idx;
-                        eid = eid + 1;
-                    }
-                }
+        int32_t first_row = (int32_t)(tile_ptr[tid] & ~DIRTY);
+        for (int64_t q = tid * T; q < (tid + 1) * T; q++) {      /* CSR order = bit_flag's order */
+            if (!bit_flag[q]) continue;
+            if (empty_offset) {
+                while (row_ptr[owner + 1] <= q) owner++;         /* q < nnz = row_ptr[m]: stops at a row < m */
+                empty_offset[written] = owner - first_row;
             }
+            written++;
         }
-        run += length;
     }
-    empty_offset_ptr[pc] = run;
+    empty_offset_ptr[pc] = written;
 }
 
 /* ------------------------------------------------------------------ */
