@@ -224,9 +224,18 @@ def csr5l_get_arrays(h, check=True):
     return dict(zip(["tile_ptr", "tile_desc", "empty_offset_ptr", "empty_offset"], [a.value for a in v]))
 
 
+_shapes: dict = {}      # handle -> (m, n), so that an SpMV call costs no extra library call
+
+
 def _xy(h, x, y, value):
     """x and y of an SpMV: element type of the entry point, at least n and m elements."""
-    m, n = csr5_get_shape(h) if h else (0, 0)
+    if not h:
+        m, n = 0, 0
+    else:
+        mn = _shapes.get(h)
+        if mn is None:
+            mn = _shapes[h] = csr5_get_shape(h)
+        m, n = mn
     return _arr(x, [value], n, "x"), _arr(y, [value], m, "y")
 
 
@@ -274,6 +283,7 @@ def csr5_to_csr(h, stream=None, check=True):
 
 
 def csr5_free(h, check=True):
+    _shapes.pop(h, None)
     return _chk(load().csr5_free(h), "csr5_free", check)
 
 

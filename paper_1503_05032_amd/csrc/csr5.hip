@@ -237,8 +237,17 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
     if (empty && r == 0) raise_status(status, CSR5_STATUS_HAS_EMPTY_ROWS);
     // Does some tile start more than LOOK entries into this row?  The last tile
     // boundary inside the row is the farthest from its start.
+    // One voice per workgroup, and an ordinary load first (it may be served by a
+    // cache; seeing an old 0 only costs a redundant OR): a matrix with many long
+    // rows would otherwise queue ten thousand wavefronts at the status word.
     const bool far = in && !bad && a != b && ((int64_t(b) - 1) / T) * T - int64_t(a) > LOOK;
-    if (__ballot(far) != 0ull && lane == 0) raise_status(status, STATUS_NEEDS_CARRY);
+    __shared__ int wg_far;
+    if (threadIdx.x == 0) wg_far = 0;
+    __syncthreads();
+    if (__ballot(far) != 0ull && lane == 0) wg_far = 1;
+    __syncthreads();
+    if (threadIdx.x == 0 && wg_far && !(*static_cast<const uint32_t*>(status) & STATUS_NEEDS_CARRY))
+        atomicOr(status, STATUS_NEEDS_CARRY);
     const int t = (empty && a > 0) ? int((a - 1) / T) : -1 - lane;
     const int tprev = __shfl_up(t, 1, OMEGA);
     if (t >= 0 && t < p && (lane == 0 || tprev != t) &&

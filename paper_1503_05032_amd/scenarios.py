@@ -72,6 +72,7 @@ def measure(a, reps=50, sigma=0):
         torch.cuda.synchronize()
         conv.append(e0.elapsed_time(e1))
     t_pre = float(np.median(conv))
+    assert B.csr5_status(h) & 3 == 0              # the handle learns which launches the matrix needs
     t_csr5 = _time(torch, lambda: B.csr5_spmv_ex(h, x, y), reps)
     B.csr5_free(h)
     tc = t_csr[best_csr]
