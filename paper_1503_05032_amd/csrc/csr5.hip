@@ -235,19 +235,9 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
     // nonzero mark no tile, and row 0 speaks for them.
     const bool empty = in && !bad && a == b;
     if (empty && r == 0) raise_status(status, CSR5_STATUS_HAS_EMPTY_ROWS);
-    // Does some tile start more than LOOK entries into this row?  The last tile
-    // boundary inside the row is the farthest from its start.
-    // One voice per workgroup, and an ordinary load first (it may be served by a
-    // cache; seeing an old 0 only costs a redundant OR): a matrix with many long
-    // rows would otherwise queue ten thousand wavefronts at the status word.
-    const bool far = in && !bad && a != b && ((int64_t(b) - 1) / T) * T - int64_t(a) > LOOK;
-    __shared__ int wg_far;
-    if (threadIdx.x == 0) wg_far = 0;
-    __syncthreads();
-    if (__ballot(far) != 0ull && lane == 0) wg_far = 1;
-    __syncthreads();
-    if (threadIdx.x == 0 && wg_far && !(*static_cast<const uint32_t*>(status) & STATUS_NEEDS_CARRY))
-        atomicOr(status, STATUS_NEEDS_CARRY);
+    const bool nonempty = in && !bad && a != b;
+    const IT a_tile = nonempty ? IT(a / T) : IT(0);
+    const int a_off = nonempty ? int(a - a_tile * T) : 0;
     const int t = (empty && a > 0) ? int((a - 1) / T) : -1 - lane;
     const int tprev = __shfl_up(t, 1, OMEGA);
     if (t >= 0 && t < p && (lane == 0 || tprev != t) &&
@@ -262,8 +252,8 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
     uint64_t word = ~uint64_t(lane);                      // no real word index, different in every lane
     uint32_t bits = 0;
     if (sets) {
-        const int tile = int(a / T);
-        const int w = int(a - IT(tile) * T);
+        const int tile = int(a_tile);
+        const int w = a_off;
         const int i = w / sigma;
         const int j = w - i * sigma;
         word = (uint64_t(tile) * W + (j >> 5)) * OMEGA + i;
@@ -289,6 +279,7 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
 template <typename IT>
 __global__ void __launch_bounds__(256)
 k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
+            const uint32_t* __restrict__ tile_head, uint32_t* __restrict__ wg_far,
             uint32_t* __restrict__ desc, IT* __restrict__ eop, uint32_t* __restrict__ status) {
     const int lane = lane_id();
     const int nwaves = int(gridDim.x) * (blockDim.x / OMEGA);
@@ -296,7 +287,7 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
     // A tile is 256 bytes of work and one memory round trip: the grid is capped,
     // every wavefront takes several tiles, and it requests UNROLL of them at once.
     constexpr int UNROLL = 4;
-    bool met_marked = false;
+    bool met_marked = false, met_far = false;
     for (int t0 = first; t0 < pc; t0 += UNROLL * nwaves) {
         uint64_t flags_u[UNROLL];
         bool dirty_u[UNROLL];
@@ -310,6 +301,7 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
                 flags_u[u] = desc[base];
                 if (sigma > 32) flags_u[u] |= uint64_t(desc[base + OMEGA]) << 32;
                 dirty_u[u] = (tile_ptr[tile] & Index<IT>::DIRTY) != 0;
+                met_far |= tile_head[tile] > uint32_t(LOOK);   // the tile starts far into a row
             }
         }
 #pragma unroll
@@ -352,6 +344,12 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
     __syncthreads();
     if (threadIdx.x == 0 && wg_met_marked)
         raise_status(status, CSR5_STATUS_HAS_DIRTY | CSR5_STATUS_HAS_EMPTY_ROWS | STATUS_SCAN_NEEDED);
+    // "some tile starts more than LOOK entries into a row" (the SpMV then needs its
+    // carry array) does not go to the status word from here -- thousands of
+    // workgroups saying so cost 10 us -- but into one word per workgroup, which
+    // the scan that follows collects.
+    const int any_far = __syncthreads_or(int(met_far));
+    if (threadIdx.x == 0) wg_far[blockIdx.x] = uint32_t(any_far != 0);
 }
 
 // ----------------------------------------------------------------------------
@@ -362,6 +360,7 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
 // every chunk gets a workgroup (local scan + chunk total) and a second launch
 // adds to every chunk the sum of the totals before it.
 // ----------------------------------------------------------------------------
+constexpr uint32_t MAX_DESC_WG = 4096;     // workgroups of k_tile_desc
 constexpr int SCAN_THREADS = 1024, SCAN_ITEMS = 8, SCAN_CHUNK = SCAN_THREADS * SCAN_ITEMS;
 constexpr int SCAN_SINGLE = 4 * SCAN_CHUNK;
 
@@ -423,10 +422,24 @@ __device__ __forceinline__ void scan_epilogue(int pc, int p, IT total, IT* __res
         atomicOr(status, CSR5_STATUS_HAS_DIRTY | CSR5_STATUS_HAS_EMPTY_ROWS);
 }
 
+// Did some workgroup of k_tile_desc (nwg of them) meet a tile that starts more
+// than LOOK entries into a row, or does the incomplete tile?  Every thread of the
+// workgroup must call this; all get the answer.
+__device__ __forceinline__ bool any_tile_far(const uint32_t* __restrict__ wg_far, int nwg,
+                                             const uint32_t* __restrict__ tile_head, int pc, int p) {
+    int far = 0;
+    for (int w = threadIdx.x; w < nwg; w += blockDim.x) far |= int(wg_far[w]);
+    if (threadIdx.x == 0 && p > pc) far |= int(tile_head[pc] > uint32_t(LOOK));
+    return __syncthreads_or(far) != 0;
+}
+
 template <typename IT>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_eop(int pc, int p, IT* __restrict__ eop, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
+           const uint32_t* __restrict__ tile_head, const uint32_t* __restrict__ wg_far, int nwg,
            uint32_t* __restrict__ status) {
+    const bool far = any_tile_far(wg_far, nwg, tile_head, pc, p);
+    if (far && threadIdx.x == 0) atomicOr(status, STATUS_NEEDS_CARRY);
     IT total = 0;
     if (*status & STATUS_SCAN_NEEDED)
         for (int64_t base = 0; base < pc; base += SCAN_CHUNK) total += scan_chunk(eop, base, int64_t(pc), total);
@@ -447,8 +460,13 @@ k_scan_chunks(int pc, IT* __restrict__ eop, IT* __restrict__ chunk_sum, const ui
 template <typename IT>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_finish(int pc, int p, IT* __restrict__ eop, const IT* __restrict__ chunk_sum,
-              const typename Index<IT>::tp_t* __restrict__ tile_ptr, uint32_t* __restrict__ status) {
+              const typename Index<IT>::tp_t* __restrict__ tile_ptr, const uint32_t* __restrict__ tile_head,
+              const uint32_t* __restrict__ wg_far, int nwg, uint32_t* __restrict__ status) {
     const int b = blockIdx.x, last = int(gridDim.x) - 1;
+    if (b == last) {                                       // uniform over the workgroup
+        const bool far = any_tile_far(wg_far, nwg, tile_head, pc, p);
+        if (far && threadIdx.x == 0) atomicOr(status, STATUS_NEEDS_CARRY);
+    }
     if (!(*status & STATUS_SCAN_NEEDED)) {
         if (b == last && threadIdx.x == 0) scan_epilogue(pc, p, IT(0), eop, tile_ptr, status);
         return;
@@ -566,6 +584,9 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
     VT* buf = reinterpret_cast<VT*>(lds[wave]);
     int32_t* ibuf = reinterpret_cast<int32_t*>(lds[wave]);
     bool bad = false;
+    // The copy of the tile's last entries is for the SpMV's look-behind, which a
+    // matrix with a tile far into a row never uses (k_rows has said so by now).
+    const bool keep_last = !BACK && last_val && last_col && !(*status & STATUS_NEEDS_CARRY);
 
     // ---- val: HBM -> registers -> LDS -> registers -> HBM
     VT v[SIGMA];
@@ -573,7 +594,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
 #pragma unroll
         for (int k = 0; k < SIGMA; k++) v[k] = __builtin_nontemporal_load(&val[base + k * OMEGA + lane]);
         // the tile's last LOOK entries, still in CSR order, for the SpMV's look-behind
-        if (!BACK && last_val && lane >= OMEGA - LOOK) last_val[size_t(tile) * last_val_stride<VT>() + (lane - (OMEGA - LOOK))] = v[SIGMA - 1];
+        if (!BACK && keep_last && lane >= OMEGA - LOOK) last_val[size_t(tile) * last_val_stride<VT>() + (lane - (OMEGA - LOOK))] = v[SIGMA - 1];
         if (!BACK) {
 #pragma unroll
             for (int k = 0; k < SIGMA; k++) {
@@ -609,7 +630,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
             c[k] = __builtin_nontemporal_load(&col_idx[base + k * OMEGA + lane]);
             bad |= (c[k] < 0) | (c[k] >= n);
         }
-        if (!BACK && last_col && lane >= OMEGA - LOOK) last_col[size_t(tile) * LAST_COL_STRIDE + (lane - (OMEGA - LOOK))] = c[SIGMA - 1];
+        if (!BACK && keep_last && lane >= OMEGA - LOOK) last_col[size_t(tile) * LAST_COL_STRIDE + (lane - (OMEGA - LOOK))] = c[SIGMA - 1];
         if (!BACK) {
 #pragma unroll
             for (int k = 0; k < SIGMA; k++) {
@@ -966,7 +987,8 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         // at once the kernel ran out of the 256 a wavefront can have (sigma >= 42:
         // spills into accumulator registers, one wavefront per SIMD).
         constexpr int GROUP = SIGMA > 46 ? 8 : (SIGMA > 32 ? 16 : SIGMA);
-        if constexpr (CAN_LOOK) head_x = x[head_c];
+        // (without the look-behind the record holds nothing: the conversion did not fill it)
+        if constexpr (CAN_LOOK) head_x = x[look ? head_c : 0];
 #pragma unroll
         for (int k0 = 0; k0 < SIGMA; k0 += GROUP) {
 #pragma unroll
@@ -1243,7 +1265,7 @@ struct csr5_handle_s {
 namespace {
 
 struct Layout {
-    size_t off_tile_ptr, off_tile_head, off_desc, off_eop, off_eo, off_carry, off_last, off_scan, off_status, total;
+    size_t off_tile_ptr, off_tile_head, off_desc, off_eop, off_eo, off_carry, off_last, off_scan, off_wg_far, off_status, total;
     bool has_last;
     size_t ndesc, eo_cap;
 };
@@ -1265,6 +1287,7 @@ Layout make_layout(int32_t m, const Geom& g, bool wide) {
     L.has_last = look_sigma(g.sigma) && g.pc > 0;
     L.off_last = o;     o += L.has_last ? align256(size_t(g.pc) * LAST_REC_BYTES) : 0;
     L.off_scan = o;     o += align256((size_t(g.pc) / SCAN_CHUNK + 1) * isz);   // chunk totals of the scan
+    L.off_wg_far = o;   o += align256(size_t(MAX_DESC_WG) * 4);                  // one word per workgroup of k_tile_desc
     L.off_status = o;   o += 256;
     L.total = o;
     return L;
@@ -1407,22 +1430,26 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
                            row_ptr, g.sigma, g.T, g.W, g.p, g.pc, tile_ptr, h->tile_desc, h->status);
         e = hipGetLastError();
     }
+    uint32_t* const wg_far = reinterpret_cast<uint32_t*>(basep + L.off_wg_far);
+    int n_desc_wg = 0;
     if (e == hipSuccess && g.pc > 0) {   // step 3b
         uint32_t nb = uint32_t((g.pc + 3) / 4);
-        if (nb > 4096) nb = 4096;                          // 64 wavefronts per CU
+        if (nb > MAX_DESC_WG) nb = MAX_DESC_WG;            // 64 wavefronts per CU
+        n_desc_wg = int(nb);
         hipLaunchKernelGGL(k_tile_desc<IT>, dim3(nb), dim3(256), 0, s, g.sigma, g.W,
-                           g.ybits, g.pc, tile_ptr, h->tile_desc, eop, h->status);
+                           g.ybits, g.pc, tile_ptr, h->tile_head, wg_far, h->tile_desc, eop, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && g.pc <= SCAN_SINGLE) {
-        hipLaunchKernelGGL(k_scan_eop<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, tile_ptr, h->status);
+        hipLaunchKernelGGL(k_scan_eop<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, tile_ptr, h->tile_head, wg_far,
+                           n_desc_wg, h->status);
         e = hipGetLastError();
     } else if (e == hipSuccess) {
         IT* chunk_sum = reinterpret_cast<IT*>(basep + L.off_scan);
         const int nchunks = (g.pc + SCAN_CHUNK - 1) / SCAN_CHUNK;      // <= 2^26 / 2^13 = SCAN_CHUNK
         hipLaunchKernelGGL(k_scan_chunks<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, eop, chunk_sum, h->status);
         hipLaunchKernelGGL(k_scan_finish<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, chunk_sum,
-                           tile_ptr, h->status);
+                           tile_ptr, h->tile_head, wg_far, n_desc_wg, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && g.pc > 0 && m > 0) {
