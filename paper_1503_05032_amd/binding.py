@@ -122,6 +122,9 @@ def _ptr(t):
     return t.data_ptr() or None
 
 
+_DTYPES: dict = {}      # filled on first use (torch is imported by load())
+
+
 def _arr(t, dtypes, min_numel, name):
     """Device address of a torch tensor after checking what the library cannot
     check: element type and length.  A wrong one would make a kernel read or
@@ -129,9 +132,11 @@ def _arr(t, dtypes, min_numel, name):
     (raw device addresses) and None pass through unchecked."""
     if t is None or isinstance(t, int):
         return _ptr(t)
-    import torch
-    names = {"i32": torch.int32, "i64": torch.int64, "f64": torch.float64, "f32": torch.float32, "u8": torch.uint8}
-    if t.dtype not in [names[d] for d in dtypes]:
+    if not _DTYPES:
+        import torch
+        _DTYPES.update({"i32": torch.int32, "i64": torch.int64, "f64": torch.float64, "f32": torch.float32,
+                        "u8": torch.uint8})
+    if not any(t.dtype is _DTYPES[d] for d in dtypes):
         raise ValueError(f"{name}: expected dtype {' or '.join(dtypes)}, got {t.dtype}")
     if t.numel() < min_numel:
         raise ValueError(f"{name}: needs at least {min_numel} elements, has {t.numel()}")

@@ -1080,7 +1080,7 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
 // ----------------------------------------------------------------------------
 template <typename VT, typename IT>
 __global__ void __launch_bounds__(256)
-k_spmv_fixup(int m, int ntiles, const IT* __restrict__ row_ptr,
+k_spmv_fixup(int m, int ntiles,
              const typename Index<IT>::tp_t* __restrict__ tile_ptr, const VT* __restrict__ carry,
              VT* __restrict__ y, const uint32_t* __restrict__ status) {
     // rows are below 2^31 whatever the index width; 0xfff... marks "no tile"
@@ -1524,8 +1524,9 @@ int csr5_convert(int32_t m, int32_t n, int32_t nnz, const int32_t* row_ptr, int3
 
 }  // extern "C"
 
-// One SpMV: the tile kernel, then the carry fix-up.  `which` selects the launches
-// (measurement only): bit 0 the tile kernel, bit 1 the fix-up.
+// One SpMV: the tile kernel, then the carry fix-up if this matrix needs it.
+// `which` selects the launches (measurement only): bit 0 the tile kernel, bit 1
+// the fix-up.
 constexpr int LAUNCH_TILES = 1, LAUNCH_FIXUP = 2, LAUNCH_BOTH = 3;
 
 template <typename VT, typename IT>
@@ -1563,7 +1564,7 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, in
     if ((which & LAUNCH_FIXUP) && carries && h->g.p > 0) {
         int ntiles = h->g.p;                                  // one thread per tile
         size_t nb = (size_t(ntiles) + 255) / 256;
-        hipLaunchKernelGGL((k_spmv_fixup<VT, IT>), dim3(uint32_t(nb)), dim3(256), 0, s, h->m, ntiles, row_ptr,
+        hipLaunchKernelGGL((k_spmv_fixup<VT, IT>), dim3(uint32_t(nb)), dim3(256), 0, s, h->m, ntiles,
                            tile_ptr, carry, y, h->status);
         if (hipGetLastError() != hipSuccess) return CSR5_EHIP;
     }

@@ -220,10 +220,15 @@ def test_csr_baselines_match_oracle():
                                       check=False) == B.CSR5_EINVAL
 
 
-def test_side_stream_and_graph_replay():
+@pytest.mark.parametrize("kind", ["carry_array", "look_behind"])
+def test_side_stream_and_graph_replay(kind):
     """csr5_spmv_ex only enqueues kernels: it runs on any stream and can be
-    captured into a HIP graph; every replay must equal the eager result."""
-    a = wl.config(4, scale=0.02)           # has empty rows, long rows and an incomplete tile
+    captured into a HIP graph; every replay must equal the eager result.  Both
+    forms of the SpMV: two kernels (a matrix with long rows) and one."""
+    if kind == "carry_array":
+        a = wl.config(4, scale=0.02)       # has empty rows, long rows and an incomplete tile
+    else:
+        a = wl.config(2, scale=0.03)       # 27-point stencil: every row is finished by the tile it ends in
     d = DeviceCsr(a)
     h = convert(d, sigma=0)
     y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, a.x)

@@ -119,3 +119,32 @@ def test_structured_case_catalogue():
     assert not rep.sorted_distinct
     r = np.repeat(np.arange(rep.m), np.diff(rep.row_ptr))
     assert np.unique(np.stack([r, rep.col_idx]), axis=1).shape[1] < rep.nnz          # it does repeat entries
+
+
+
+def test_measured_traffic_file_is_well_formed():
+    """bench.py's roofline.traffic comes from a tracked summary of offline rocprofv3
+    runs: every line names workload, sigma, dtype, the two counters, the commit it
+    was measured at and the kernel; bench.py's reader scales them as documented."""
+    import os
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    assert os.path.exists(bench.TRAFFIC_FILE)
+    seen = set()
+    for line in open(bench.TRAFFIC_FILE):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = line.split()
+        assert len(f) == 7, line
+        w, sigma, dtype = int(f[0]), int(f[1]), f[2]
+        fetch, write = float(f[3]), float(f[4])
+        assert 1 <= w <= 8 and 1 <= sigma <= 48 and dtype in ("f64", "f32")
+        assert fetch > 0 and write > 0 and len(f[5]) >= 7 and f[6].startswith("k_spmv<")
+        t = bench.measured_traffic(w, sigma, dtype, 1.0)
+        assert t["bytes"] == int((2.0 * fetch + write) * 1024) and t["measured_at_commit"] == f[5]
+        seen.add(w)
+    assert {2, 3, 4, 5}.issubset(seen)                 # every configuration with a traffic-bound kernel
+    assert bench.measured_traffic(2, 16, "f64", 2.0) is None          # a size sweep has no stored figure
+    assert bench.measured_traffic(2, 7, "f64", 1.0) is None
