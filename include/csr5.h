@@ -86,7 +86,7 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * 8 <= sigma <= 32 a copy of every complete tile's last 32 (col_idx, val) pairs in CSR
  * order (384 bytes per tile; it lets a tile finish a row that began in the
  * previous tile without a second kernel) + the conversion's scratch
- * (p_c/8192 + 1 + 4096 words) + a status word, each rounded up to 256 bytes.
+ * (p_c/8192 + 1 + 8192 words) + a status word, each rounded up to 256 bytes.
  * Returns 0 for invalid arguments.
  */
 size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma);

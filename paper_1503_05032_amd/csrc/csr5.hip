@@ -180,12 +180,14 @@ template <typename IT>
 __global__ void __launch_bounds__(256)
 k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p,
            typename Index<IT>::tp_t* __restrict__ tile_ptr, uint32_t* __restrict__ tile_head,
-           uint32_t* __restrict__ desc, size_t ndesc, uint32_t* __restrict__ status) {
+           uint32_t* __restrict__ wg_far, uint32_t* __restrict__ desc, size_t ndesc,
+           uint32_t* __restrict__ status) {
     using tp_t = typename Index<IT>::tp_t;
     size_t gid = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
     size_t stride = size_t(gridDim.x) * blockDim.x;
     for (size_t k = gid; k < ndesc; k += stride) desc[k] = 0u;
     if (gid == 0) *status = 0u;
+    int far = 0;
     for (size_t t = gid; t <= size_t(p); t += stride) {
         int64_t bnd = int64_t(t) * T;
         const int row = count_le(row_ptr, m + 1, bnd) - 1;
@@ -196,7 +198,14 @@ k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p,
         int64_t head = 0;
         if (t < size_t(p) && row >= 0 && row < m) head = bnd - int64_t(row_ptr[row]);
         tile_head[t] = uint32_t(head < 0 ? 0 : (head > LOOK + 1 ? LOOK + 1 : head));
+        far |= int(head > LOOK);
     }
+    // "Some tile starts more than LOOK entries into a row" (the SpMV then needs its
+    // carry array) does not go to the status word from here -- this launch also
+    // clears that word, and thousands of workgroups saying so would queue at it --
+    // but into one word per workgroup, which the scan kernel collects.
+    far = __syncthreads_or(far);
+    if (threadIdx.x == 0) wg_far[blockIdx.x] = uint32_t(far != 0);
 }
 
 // ----------------------------------------------------------------------------
@@ -279,7 +288,6 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
 template <typename IT>
 __global__ void __launch_bounds__(256)
 k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
-            const uint32_t* __restrict__ tile_head, uint32_t* __restrict__ wg_far,
             uint32_t* __restrict__ desc, IT* __restrict__ eop, uint32_t* __restrict__ status) {
     const int lane = lane_id();
     const int nwaves = int(gridDim.x) * (blockDim.x / OMEGA);
@@ -287,7 +295,7 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
     // A tile is 256 bytes of work and one memory round trip: the grid is capped,
     // every wavefront takes several tiles, and it requests UNROLL of them at once.
     constexpr int UNROLL = 4;
-    bool met_marked = false, met_far = false;
+    bool met_marked = false;
     for (int t0 = first; t0 < pc; t0 += UNROLL * nwaves) {
         uint64_t flags_u[UNROLL];
         bool dirty_u[UNROLL];
@@ -301,7 +309,6 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
                 flags_u[u] = desc[base];
                 if (sigma > 32) flags_u[u] |= uint64_t(desc[base + OMEGA]) << 32;
                 dirty_u[u] = (tile_ptr[tile] & Index<IT>::DIRTY) != 0;
-                met_far |= tile_head[tile] > uint32_t(LOOK);   // the tile starts far into a row
             }
         }
 #pragma unroll
@@ -344,12 +351,6 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
     __syncthreads();
     if (threadIdx.x == 0 && wg_met_marked)
         raise_status(status, CSR5_STATUS_HAS_DIRTY | CSR5_STATUS_HAS_EMPTY_ROWS | STATUS_SCAN_NEEDED);
-    // "some tile starts more than LOOK entries into a row" (the SpMV then needs its
-    // carry array) does not go to the status word from here -- thousands of
-    // workgroups saying so cost 10 us -- but into one word per workgroup, which
-    // the scan that follows collects.
-    const int any_far = __syncthreads_or(int(met_far));
-    if (threadIdx.x == 0) wg_far[blockIdx.x] = uint32_t(any_far != 0);
 }
 
 // ----------------------------------------------------------------------------
@@ -360,7 +361,7 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
 // every chunk gets a workgroup (local scan + chunk total) and a second launch
 // adds to every chunk the sum of the totals before it.
 // ----------------------------------------------------------------------------
-constexpr uint32_t MAX_DESC_WG = 4096;     // workgroups of k_tile_desc
+constexpr uint32_t MAX_TILE_PTR_WG = 8192;     // workgroups of k_tile_ptr
 constexpr int SCAN_THREADS = 1024, SCAN_ITEMS = 8, SCAN_CHUNK = SCAN_THREADS * SCAN_ITEMS;
 constexpr int SCAN_SINGLE = 4 * SCAN_CHUNK;
 
@@ -422,14 +423,12 @@ __device__ __forceinline__ void scan_epilogue(int pc, int p, IT total, IT* __res
         atomicOr(status, CSR5_STATUS_HAS_DIRTY | CSR5_STATUS_HAS_EMPTY_ROWS);
 }
 
-// Did some workgroup of k_tile_desc (nwg of them) meet a tile that starts more
-// than LOOK entries into a row, or does the incomplete tile?  Every thread of the
-// workgroup must call this; all get the answer.
-__device__ __forceinline__ bool any_tile_far(const uint32_t* __restrict__ wg_far, int nwg,
-                                             const uint32_t* __restrict__ tile_head, int pc, int p) {
+// Did some workgroup of k_tile_ptr (nwg of them) meet a tile that starts more
+// than LOOK entries into a row?  Every thread of the workgroup must call this;
+// all get the answer.
+__device__ __forceinline__ bool any_tile_far(const uint32_t* __restrict__ wg_far, int nwg) {
     int far = 0;
     for (int w = threadIdx.x; w < nwg; w += blockDim.x) far |= int(wg_far[w]);
-    if (threadIdx.x == 0 && p > pc) far |= int(tile_head[pc] > uint32_t(LOOK));
     return __syncthreads_or(far) != 0;
 }
 
@@ -438,7 +437,7 @@ __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_eop(int pc, int p, IT* __restrict__ eop, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
            const uint32_t* __restrict__ tile_head, const uint32_t* __restrict__ wg_far, int nwg,
            uint32_t* __restrict__ status) {
-    const bool far = any_tile_far(wg_far, nwg, tile_head, pc, p);
+    const bool far = any_tile_far(wg_far, nwg);
     if (far && threadIdx.x == 0) atomicOr(status, STATUS_NEEDS_CARRY);
     IT total = 0;
     if (*status & STATUS_SCAN_NEEDED)
@@ -464,7 +463,7 @@ k_scan_finish(int pc, int p, IT* __restrict__ eop, const IT* __restrict__ chunk_
               const uint32_t* __restrict__ wg_far, int nwg, uint32_t* __restrict__ status) {
     const int b = blockIdx.x, last = int(gridDim.x) - 1;
     if (b == last) {                                       // uniform over the workgroup
-        const bool far = any_tile_far(wg_far, nwg, tile_head, pc, p);
+        const bool far = any_tile_far(wg_far, nwg);
         if (far && threadIdx.x == 0) atomicOr(status, STATUS_NEEDS_CARRY);
     }
     if (!(*status & STATUS_SCAN_NEEDED)) {
@@ -836,7 +835,9 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     constexpr int PITCH = TransposeShape<SIGMA>::PITCH;
     using flag_t = typename FlagWord<SIGMA>::type;
     using tp_t = typename Index<IT>::tp_t;
-    __shared__ double lds[WAVES][OMEGA * PITCH];
+    // one slot per tile entry: a column index on the way in, an x value on the way back,
+    // a segment sum at the end (so single precision needs half the space)
+    __shared__ VT lds[WAVES][OMEGA * PITCH];
 
     const uint32_t st = *status;      // consulted below, after the streaming loads are in flight
     // Rows that cross a tile boundary are completed by look-behind in the whole
@@ -1287,7 +1288,7 @@ Layout make_layout(int32_t m, const Geom& g, bool wide) {
     L.has_last = look_sigma(g.sigma) && g.pc > 0;
     L.off_last = o;     o += L.has_last ? align256(size_t(g.pc) * LAST_REC_BYTES) : 0;
     L.off_scan = o;     o += align256((size_t(g.pc) / SCAN_CHUNK + 1) * isz);   // chunk totals of the scan
-    L.off_wg_far = o;   o += align256(size_t(MAX_DESC_WG) * 4);                  // one word per workgroup of k_tile_desc
+    L.off_wg_far = o;   o += align256(size_t(MAX_TILE_PTR_WG) * 4);              // one word per workgroup of k_tile_ptr
     L.off_status = o;   o += 256;
     L.total = o;
     return L;
@@ -1417,12 +1418,15 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     IT* const eop = static_cast<IT*>(h->eop);
 
     hipError_t e = hipSuccess;
+    uint32_t* const wg_far = reinterpret_cast<uint32_t*>(basep + L.off_wg_far);
+    int n_far_wg = 0;
     {   // step 2a (+ clearing)
         size_t work = L.ndesc > size_t(g.p) + 1 ? L.ndesc : size_t(g.p) + 1;
         size_t nb = (work + 255) / 256;
-        if (nb > 8192) nb = 8192;
+        if (nb > MAX_TILE_PTR_WG) nb = MAX_TILE_PTR_WG;
+        n_far_wg = int(nb);
         hipLaunchKernelGGL(k_tile_ptr<IT>, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p,
-                           tile_ptr, h->tile_head, h->tile_desc, L.ndesc, h->status);
+                           tile_ptr, h->tile_head, wg_far, h->tile_desc, L.ndesc, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && m > 0) {   // steps 2b + 3a
@@ -1430,26 +1434,23 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
                            row_ptr, g.sigma, g.T, g.W, g.p, g.pc, tile_ptr, h->tile_desc, h->status);
         e = hipGetLastError();
     }
-    uint32_t* const wg_far = reinterpret_cast<uint32_t*>(basep + L.off_wg_far);
-    int n_desc_wg = 0;
     if (e == hipSuccess && g.pc > 0) {   // step 3b
         uint32_t nb = uint32_t((g.pc + 3) / 4);
-        if (nb > MAX_DESC_WG) nb = MAX_DESC_WG;            // 64 wavefronts per CU
-        n_desc_wg = int(nb);
+        if (nb > 4096) nb = 4096;                          // 64 wavefronts per CU
         hipLaunchKernelGGL(k_tile_desc<IT>, dim3(nb), dim3(256), 0, s, g.sigma, g.W,
-                           g.ybits, g.pc, tile_ptr, h->tile_head, wg_far, h->tile_desc, eop, h->status);
+                           g.ybits, g.pc, tile_ptr, h->tile_desc, eop, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && g.pc <= SCAN_SINGLE) {
         hipLaunchKernelGGL(k_scan_eop<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, tile_ptr, h->tile_head, wg_far,
-                           n_desc_wg, h->status);
+                           n_far_wg, h->status);
         e = hipGetLastError();
     } else if (e == hipSuccess) {
         IT* chunk_sum = reinterpret_cast<IT*>(basep + L.off_scan);
         const int nchunks = (g.pc + SCAN_CHUNK - 1) / SCAN_CHUNK;      // <= 2^26 / 2^13 = SCAN_CHUNK
         hipLaunchKernelGGL(k_scan_chunks<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, eop, chunk_sum, h->status);
         hipLaunchKernelGGL(k_scan_finish<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, chunk_sum,
-                           tile_ptr, h->tile_head, wg_far, n_desc_wg, h->status);
+                           tile_ptr, h->tile_head, wg_far, n_far_wg, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && g.pc > 0 && m > 0) {

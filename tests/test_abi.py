@@ -60,12 +60,12 @@ def test_workspace_bytes(lib):
     need = (p + 1) * 4 + pc * W * 64 * 4 + (pc + 1) * 4 + min(m + pc, pc * T) * 4 + (p + 1) * 8 + 4
     need += pc * 32 * (4 + 8)              # copy of every tile's last 32 entries (sigma >= 8)
     need += (p + 1) * 4                    # per tile: how far into its first row it starts
-    need += 4096 * 4                       # conversion scratch: one word per workgroup of the descriptor kernel
+    need += 8192 * 4                       # conversion scratch: one word per workgroup of the tile_ptr kernel
     got = B.csr5_workspace_bytes(m, nnz, sigma)
     assert need <= got <= need + 11 * 256
     # no such copy below sigma 8
     p4, pc4 = -(-nnz // 256), nnz // 256
-    need4 = (p4 + 1) * 4 + pc4 * 64 * 4 + (pc4 + 1) * 4 + min(m + pc4, pc4 * 256) * 4 + (p4 + 1) * 8 + 4 + (p4 + 1) * 4 + 4096 * 4
+    need4 = (p4 + 1) * 4 + pc4 * 64 * 4 + (pc4 + 1) * 4 + min(m + pc4, pc4 * 256) * 4 + (p4 + 1) * 8 + 4 + (p4 + 1) * 4 + 8192 * 4
     assert need4 <= B.csr5_workspace_bytes(m, nnz, 4) <= need4 + 9 * 256
 
 
@@ -86,7 +86,7 @@ def test_wide_variant_limits(lib):
     p, pc = -(-nnz // T), nnz // T
     W = oracle.desc_words(64, sigma)
     need = (p + 1) * 8 + pc * W * 64 * 4 + (pc + 1) * 8 + min(m + pc, pc * T) * 4 + (p + 1) * 8 + 4
-    need += pc * 32 * (4 + 8) + (p + 1) * 4 + 4096 * 4
+    need += pc * 32 * (4 + 8) + (p + 1) * 4 + 8192 * 4
     got = B.csr5l_workspace_bytes(m, nnz, sigma)
     assert need <= got <= need + 11 * 256
     # beyond 2^31 nonzeros; the limit is the number of tiles (2^26 - 5)
