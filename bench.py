@@ -70,6 +70,16 @@ def measured_traffic(workload, sigma, dtype, scale):
     return None
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown CPU"
+
+
 def git_head():
     try:
         return subprocess.check_output(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"],
@@ -477,7 +487,7 @@ def main():
             "cores": 1,
             "kind": "oracle",
             "sample": f"{reps} {what} (sequential Algorithm 1, gcc -O2), "
-                      f"{t_acc:.1f} s of CPU time; host has {os.cpu_count()} logical CPUs",
+                      f"{t_acc:.1f} s of CPU time; host has {os.cpu_count()} logical CPUs ({cpu_model()})",
         }
         # the same oracle loop with the rows shared among all host cores (extra figure)
         reps2, t_acc2, threads = 0, 0.0, 1

@@ -81,7 +81,7 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * nnz nonzeros at the given sigma (0 = the value csr5_sigma_auto picks).  An
  * upper bound computable on the host: tile_ptr (p+1 words) + tile_desc
  * (p_c*W*64 words) + empty_offset_ptr (p_c+1 words) + empty_offset (at most
- * min(m + p_c, p_c*T) words) + the SpMV's auxiliary array (p+1 doubles) + one
+ * min(m + p_c, p_c*T) words) + the SpMV's four auxiliary arrays (p+1 doubles each) + one
  * word per tile saying how far into its first row the tile starts (p+1) + for
  * 8 <= sigma <= 32 a copy of every complete tile's last 32 (col_idx, val) pairs in CSR
  * order (384 bytes per tile; it lets a tile finish a row that began in the
@@ -150,8 +150,9 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, i
  * and y must not overlap.  Asynchronous.  Summation order differs from CSR
  * order; rows summed through the auxiliary array by more than one wavefront and
  * rows cut inside the incomplete tile are added up atomically, so their last
- * bits may differ between runs.  The auxiliary array lives in the handle: calls
- * on ONE handle must not overlap in time (use one stream, or order them).
+ * bits may differ between runs.  The handle holds four auxiliary arrays, taken
+ * in turn by successive calls: up to four SpMVs on ONE handle may be in flight at
+ * the same time (on different streams); a fifth must be ordered after the first.
  */
 int csr5_spmv(csr5_handle_t h, const double *x, double *y);
 int csr5_spmv_ex(csr5_handle_t h, const double *x, double *y, void *hip_stream);

@@ -362,6 +362,7 @@ k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t*
 // adds to every chunk the sum of the totals before it.
 // ----------------------------------------------------------------------------
 constexpr uint32_t MAX_TILE_PTR_WG = 8192;     // workgroups of k_tile_ptr
+constexpr uint32_t CARRY_SLOTS = 4;            // carry arrays per handle = SpMVs of one handle that may overlap
 constexpr int SCAN_THREADS = 1024, SCAN_ITEMS = 8, SCAN_CHUNK = SCAN_THREADS * SCAN_ITEMS;
 constexpr int SCAN_SINGLE = 4 * SCAN_CHUNK;
 
@@ -1248,7 +1249,12 @@ struct csr5_handle_s {
     void* eop;             // int32_t* or int64_t*
     int32_t* eo;
     uint32_t* status;
-    void* carry;           // one 8-byte slot per tile (incomplete one included): cross-tile sums of an SpMV
+    // Cross-tile sums of an SpMV: one 8-byte entry per tile (incomplete one included),
+    // CARRY_SLOTS such arrays taken in turn by successive calls, so that up to that
+    // many SpMVs on one handle may be in flight at once (on different streams).
+    void* carry;
+    size_t carry_slot_bytes;
+    std::atomic<uint32_t> carry_turn;
     uint32_t* tile_head;   // per tile: entries of its first row that lie before it, saturated at LOOK + 1
     // CSR-order copy of every complete tile's last LOOK entries (NULL for small sigma):
     // two views of one array of LAST_REC_BYTES-byte records
@@ -1268,7 +1274,7 @@ namespace {
 struct Layout {
     size_t off_tile_ptr, off_tile_head, off_desc, off_eop, off_eo, off_carry, off_last, off_scan, off_wg_far, off_status, total;
     bool has_last;
-    size_t ndesc, eo_cap;
+    size_t ndesc, eo_cap, carry_slot_bytes;
 };
 
 Layout make_layout(int32_t m, const Geom& g, bool wide) {
@@ -1284,7 +1290,8 @@ Layout make_layout(int32_t m, const Geom& g, bool wide) {
     L.off_desc = o;     o += align256(L.ndesc * 4);
     L.off_eop = o;      o += align256((size_t(g.pc) + 1) * isz);
     L.off_eo = o;       o += align256(L.eo_cap * 4);
-    L.off_carry = o;    o += align256((size_t(g.p) + 1) * 8);
+    L.carry_slot_bytes = align256((size_t(g.p) + 1) * 8);
+    L.off_carry = o;    o += L.carry_slot_bytes * CARRY_SLOTS;
     L.has_last = look_sigma(g.sigma) && g.pc > 0;
     L.off_last = o;     o += L.has_last ? align256(size_t(g.pc) * LAST_REC_BYTES) : 0;
     L.off_scan = o;     o += align256((size_t(g.pc) / SCAN_CHUNK + 1) * isz);   // chunk totals of the scan
@@ -1397,6 +1404,8 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     h->eop = basep + L.off_eop;
     h->eo = reinterpret_cast<int32_t*>(basep + L.off_eo);
     h->carry = basep + L.off_carry;
+    h->carry_slot_bytes = L.carry_slot_bytes;
+    h->carry_turn.store(0, std::memory_order_relaxed);
     h->tile_head = reinterpret_cast<uint32_t*>(basep + L.off_tile_head);
     h->last_val = L.has_last ? basep + L.off_last : nullptr;                               // record + 0
     h->last_col = L.has_last ? reinterpret_cast<int32_t*>(basep + L.off_last + LOOK * 8) : nullptr;
@@ -1537,7 +1546,9 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, in
     const tp_t* tile_ptr = static_cast<const tp_t*>(h->tile_ptr);
     const IT* eop = static_cast<const IT*>(h->eop);
     hipError_t e = hipSuccess;
-    VT* carry = static_cast<VT*>(carry_mem ? carry_mem : h->carry);
+    // a whole SpMV takes the next of the handle's carry arrays; partial launches (measurement) the first
+    const uint32_t turn = (which == LAUNCH_BOTH) ? h->carry_turn.fetch_add(1, std::memory_order_relaxed) % CARRY_SLOTS : 0u;
+    VT* carry = static_cast<VT*>(carry_mem ? carry_mem : static_cast<void*>(static_cast<char*>(h->carry) + turn * h->carry_slot_bytes));
     // What the matrix needs beyond its tiles is known once the host has seen the
     // status word of the conversion; until then everything is launched (the
     // kernels look at the status word themselves and return at once if idle).

@@ -602,3 +602,33 @@ def test_binding_refuses_wrong_types_and_short_arrays():
         B.csr5_spmv_ex(h, d.x.float(), d.y)
     check_spmv(d, h, "after refusals")
     B.csr5_free(h)
+
+
+def test_one_handle_on_two_streams():
+    """Up to four SpMVs of ONE handle may be in flight at once (the handle takes its
+    four auxiliary arrays in turn): two streams, two calls each, different x, then
+    a synchronisation, several rounds.  A matrix with long rows, so that every call
+    really uses its auxiliary array."""
+    a = wl.config(4, scale=0.05)
+    d = DeviceCsr(a)
+    h = convert(d, sigma=8)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    rng = np.random.default_rng(3)
+    xs = [rng.standard_normal(a.n) for _ in range(4)]
+    xd = [torch.from_numpy(x).to("cuda:0") for x in xs]
+    refs = [oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val, x) for x in xs]
+    torch.cuda.synchronize()
+    for rnd in range(5):
+        ys = [torch.full_like(d.y, float("nan")) for _ in range(4)]
+        B.csr5_spmv_ex(h, xd[0], ys[0], stream=s1)
+        B.csr5_spmv_ex(h, xd[1], ys[1], stream=s2)
+        B.csr5_spmv_ex(h, xd[2], ys[2], stream=s1)
+        B.csr5_spmv_ex(h, xd[3], ys[3], stream=s2)
+        s1.synchronize()
+        s2.synchronize()
+        for k in range(4):
+            y_ref, s = refs[k]
+            got = ys[k].cpu().numpy()[:a.m]
+            bad = np.nonzero(~(np.abs(got - y_ref) <= 1e-12 * s + 1e-300))[0]
+            assert bad.size == 0, (rnd, k, int(bad.size), int(bad[0]))
+    B.csr5_free(h)
