@@ -632,3 +632,34 @@ def test_one_handle_on_two_streams():
             bad = np.nonzero(~(np.abs(got - y_ref) <= 1e-12 * s + 1e-300))[0]
             assert bad.size == 0, (rnd, k, int(bad.size), int(bad[0]))
     B.csr5_free(h)
+
+
+@pytest.mark.parametrize("wide,seed", [(False, 31), (True, 32)])
+def test_random_short_row_matrices_take_one_kernel(wide, seed):
+    """Matrices whose rows have at most 33 entries, so that no tile can start more
+    than 32 entries into a row: for 8 <= sigma <= 32 their SpMV is the tile kernel
+    alone (the profile helper reports no second kernel), whatever the mix of empty
+    rows, and its result is the oracle's."""
+    rng = np.random.default_rng(seed)
+    for case in range(24):
+        sigma = int(rng.integers(8, 33))
+        m = int(rng.integers(200, 6000))
+        n = int(rng.integers(40, 8000))
+        top = int(rng.integers(1, 34))
+        lens = rng.integers(0, top + 1, size=m)
+        if case % 3 == 0:
+            lens *= rng.random(m) < 0.5                      # many empty rows
+        if case % 3 == 1:
+            lens = np.maximum(lens, 1)                       # none
+        a = wl.from_row_lengths(lens, n, seed=seed * 100 + case, name=f"short{case}")
+        say("short rows", case, "sigma", sigma, a.m, a.n, a.nnz, "max len", int(np.diff(a.row_ptr).max()) if a.m else 0)
+        d = DeviceCsr(a, wide=wide)
+        h = convert(d, sigma=sigma)                          # blocking: the handle knows the matrix
+        check_format(d, h, (a.name, sigma))
+        check_spmv(d, h, (a.name, sigma))
+        if not wide and a.m:
+            ms_tiles, ms_second = B.csr5_spmv_profile(h, d.x, d.y, reps=50)
+            torch.cuda.synchronize()
+            assert ms_second < 1e-3, ("a second kernel was launched", ms_second)   # 50 launches of it would take 2 us each
+            _check_y(d.y.cpu().numpy()[:a.m], a, ("after profile", case))
+        B.csr5_free(h)
