@@ -585,7 +585,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
     int32_t* ibuf = reinterpret_cast<int32_t*>(lds[wave]);
     bool bad = false;
     // The copy of the tile's last entries is for the SpMV's look-behind, which a
-    // matrix with a tile far into a row never uses (k_rows has said so by now).
+    // matrix with a tile far into a row never uses (the scan kernel has said so by now).
     const bool keep_last = !BACK && last_val && last_col && !(*status & STATUS_NEEDS_CARRY);
 
     // ---- val: HBM -> registers -> LDS -> registers -> HBM
