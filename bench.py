@@ -278,13 +278,19 @@ def measure(P, sigma_arg, steps, warmup, headline, quick):
 
     # ---------------------------------------------------------------- dominant kernel, HIP events inside the library
     ms_tiles, ms_fixup = P.spmv_profile(h, P.x, y, reps=min(max(steps, 50), 2000))
+    # what the memory system alone charges for the tile kernel's streams: a bare read
+    # of col_idx, val and the descriptors, without and with the rows of y written
+    try:
+        floor = B.csr5_stream_floor(h, torch.empty_like(y), reps=min(max(steps, 50), 2000))
+    except B.Csr5Error:
+        floor = None        # no complete tile
 
     conv = float(np.median(conv_ms))
     res = {
         "P": P, "h": h, "info": info, "sigma": info["sigma"], "parity_ok": parity_ok, "parity_scope": parity_scope,
         "B_model": B_model, "B_gather": B_gather, "copies": copies,
         "ms_warm": ms_warm, "ms_rot": ms_rot, "wall_warm": wall_warm, "wall_rot": wall_rot,
-        "ms_tiles": ms_tiles, "ms_fixup": ms_fixup, "conv_ms": conv,
+        "ms_tiles": ms_tiles, "ms_fixup": ms_fixup, "floor": floor, "conv_ms": conv,
         "conv_alloc_ms": float(np.median(conv_alloc_ms)) if conv_alloc_ms else None,
         "extras": extras,
     }
@@ -320,6 +326,9 @@ def short_entry(r):
         "convert": {"ms": round(r["conv_ms"], 4), "in_spmvs": round(r["conv_ms"] / t, 2),
                     "in_spmvs_with_hipmalloc": round(r["conv_alloc_ms"] / t, 2) if r["conv_alloc_ms"] else None},
     }
+    if r["floor"]:
+        e["tile_kernel"]["stream_floor_ms"] = {"read": round(r["floor"][0], 5), "read_and_y": round(r["floor"][1], 5)}
+        e["tile_kernel"]["kernel_over_floor"] = round(r["ms_tiles"] / r["floor"][1], 3)
     if traffic:
         e["tile_kernel"]["traffic"] = traffic["bytes"]
         e["tile_kernel"]["frac_of_peak_on_measured_traffic"] = round(gbs(traffic["bytes"], r["ms_tiles"]) / HBM_PEAK_GBS, 4)
@@ -454,6 +463,11 @@ def main():
             "kernel_ms": round(r["ms_tiles"], 5),
             "second_kernel_ms": round(r["ms_fixup"], 5),
             "bytes_per_launch": B_model,
+            "stream_floor_ms": ({"read": round(r["floor"][0], 5), "read_and_y": round(r["floor"][1], 5),
+                                 "what": "bare read of the same col_idx, val and descriptors by one wavefront per tile "
+                                         "(csr5_stream_floor), without and with the rows of y written"}
+                                if r["floor"] else None),
+            "kernel_over_floor": round(r["ms_tiles"] / r["floor"][1], 3) if r["floor"] else None,
             "timing": "HIP events inside the library around a series of launches of this kernel on one matrix (warm)",
         },
         "commit": git_head(),

@@ -296,6 +296,23 @@ int csr5s_spmv_profile(csr5_handle_t h, const float *x, float *y, void *hip_stre
                        float *ms);
 
 /*
+ * Measurement helper: what the memory system alone charges for this matrix's tile
+ * streams.  A kernel with one wavefront per complete tile, in the SpMV's tile
+ * order, that only reads the tile's col_idx, val and descriptors (the bytes the
+ * per-column loop of Algorithm 8 streams) is launched `reps` times in a row, then
+ * `reps` times again with every wavefront also storing one value to each row its
+ * tile starts (the write stream of y).  ms[0], ms[1]: mean duration per launch in
+ * milliseconds of the two series (HIP events, as above; waits for the stream).
+ * The tile kernel cannot be faster than ms[1]; the distance is what its gathers,
+ * its LDS traffic and its arithmetic cost.  y (device, y_bytes bytes: at least m
+ * values of the handle's value type, CSR5_EINVAL if fewer) is OVERWRITTEN WITH
+ * MEANINGLESS VALUES.  Works on handles of every variant; col_idx and val must
+ * be 16-byte aligned (CSR5_EINVAL otherwise, also for a matrix without a
+ * complete tile).  ms is a host array of 2 floats.
+ */
+int csr5_stream_floor(csr5_handle_t h, void *y, size_t y_bytes, void *hip_stream, int reps, float *ms);
+
+/*
  * CSR row-block baselines on the plain CSR arrays (Section 2.2.1): CSR-scalar is
  * Algorithm 1 with one thread per row; CSR-vector reduces each row with
  * lanes_per_row lanes (2, 4, ..., 64; 0 = smallest power of two >= nnz/m).

@@ -30,7 +30,7 @@ CSR5_ARRAY_TILE_PTR, CSR5_ARRAY_TILE_DESC, CSR5_ARRAY_EMPTY_OFFSET_PTR, CSR5_ARR
 # every symbol include/csr5.h declares
 SYMBOLS = [
     "csr5_sigma_auto", "csr5_workspace_bytes", "csr5_convert", "csr5_convert_ex", "csr5_spmv",
-    "csr5_spmv_ex", "csr5_spmv_static", "csr5_spmv_profile", "csr5_to_csr", "csr5_free", "csr5_status", "csr5_get_info",
+    "csr5_spmv_ex", "csr5_spmv_static", "csr5_spmv_profile", "csr5_stream_floor", "csr5_to_csr", "csr5_free", "csr5_status", "csr5_get_info",
     "csr5_get_shape", "csr5_get_arrays",
     "csr5_read_array", "csr5_strerror", "csr5_baseline_csr_scalar", "csr5_baseline_csr_vector",
     "csr5s_convert_ex", "csr5s_spmv_ex", "csr5s_spmv_profile",
@@ -87,6 +87,8 @@ def load():
     lib.csr5_spmv_static.argtypes = [vp, vp, vp, vp]
     lib.csr5_spmv_profile.restype = C.c_int
     lib.csr5_spmv_profile.argtypes = [vp, vp, vp, vp, C.c_int, C.POINTER(C.c_float)]
+    lib.csr5_stream_floor.restype = C.c_int
+    lib.csr5_stream_floor.argtypes = [vp, vp, C.c_size_t, vp, C.c_int, C.POINTER(C.c_float)]
     lib.csr5_to_csr.restype = C.c_int
     lib.csr5_to_csr.argtypes = [vp, vp]
     lib.csr5_free.restype = C.c_int
@@ -280,6 +282,15 @@ def csr5_spmv_profile(h, x, y, reps, stream=None):
     ms = (C.c_float * 2)()
     _chk(load().csr5_spmv_profile(h, *_xy(h, x, y, "f64"), _stream(stream), int(reps), ms),
          "csr5_spmv_profile", True)
+    return float(ms[0]), float(ms[1])
+
+
+def csr5_stream_floor(h, y, reps, stream=None):
+    """Mean durations in ms of a bare read of the handle's tile streams: (reads only,
+    reads plus the rows of y).  y (a handle-typed scratch vector) is overwritten."""
+    ms = (C.c_float * 2)()
+    _chk(load().csr5_stream_floor(h, _arr(y, ["f64", "f32"], 0, "y"), y.numel() * y.element_size(), _stream(stream),
+                                  int(reps), ms), "csr5_stream_floor", True)
     return float(ms[0]), float(ms[1])
 
 

@@ -1119,6 +1119,59 @@ k_spmv_fixup(int m, int ntiles,
     }
 }
 
+// ----------------------------------------------------------------------------
+// Measurement aid: what the memory system charges for the tile kernel's streams
+// alone.  One wavefront per complete tile, the same workgroup shape and tile
+// order as the tile kernel's most common instantiation; it reads the tile's
+// col_idx, val and descriptors with 16-byte non-temporal loads (all of a tile in
+// flight at once up to sigma = 16) and, if asked, stores one value to every row
+// the tile starts (the rows of y that tile's wavefront writes in an SpMV).  No
+// gathers, no LDS, no arithmetic to speak of.
+// ----------------------------------------------------------------------------
+constexpr int FLOOR_WAVES = 4;
+constexpr int FLOOR_LOADS = 12;            // 16-byte loads per lane and round
+
+template <typename VT, typename IT>
+__global__ void __launch_bounds__(FLOOR_WAVES * OMEGA)
+k_stream_floor(int m, int pc, int sigma, int W, uint32_t nb_tiles, uint32_t xcd_chunk, int write_y,
+               const typename Index<IT>::tp_t* __restrict__ tile_ptr, const uint32_t* __restrict__ tile_desc,
+               const int32_t* __restrict__ col_idx, const VT* __restrict__ val, VT* __restrict__ y,
+               uint32_t* __restrict__ sink) {
+    typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / OMEGA);
+    const int tile = int(xcd_order(blockIdx.x, nb_tiles, xcd_chunk)) * FLOOR_WAVES + wave;
+    if (tile >= pc) return;
+    const int T = OMEGA * sigma;
+    // the three streams of a tile as one sequence of 16-byte pieces
+    const i32x4* c4 = reinterpret_cast<const i32x4*>(col_idx + size_t(tile) * T);
+    const i32x4* v4 = reinterpret_cast<const i32x4*>(val + size_t(tile) * T);
+    const i32x4* d4 = reinterpret_cast<const i32x4*>(tile_desc + size_t(tile) * W * OMEGA);
+    const int n_c = T / 4, n_v = T * int(sizeof(VT)) / 16, n_d = W * OMEGA / 4;
+    const int total = n_c + n_v + n_d;
+    int32_t acc = 0;
+    for (int base = 0; base < total; base += OMEGA * FLOOR_LOADS) {
+        i32x4 r[FLOOR_LOADS];
+#pragma unroll
+        for (int u = 0; u < FLOOR_LOADS; u++) {
+            const int idx = base + u * OMEGA + lane;
+            const i32x4* src = idx < n_c ? c4 + idx : (idx < n_c + n_v ? v4 + (idx - n_c) : d4 + (idx - n_c - n_v));
+            r[u] = i32x4{0, 0, 0, 0};
+            if (idx < total) r[u] = __builtin_nontemporal_load(src);
+        }
+#pragma unroll
+        for (int u = 0; u < FLOOR_LOADS; u++) acc ^= r[u].x ^ r[u].y ^ r[u].z ^ r[u].w;
+    }
+    if (write_y) {
+        const uint32_t r0 = uint32_t(tile_ptr[tile] & Index<IT>::ROWMASK);
+        uint32_t r1 = uint32_t(tile_ptr[tile + 1] & Index<IT>::ROWMASK);
+        if (r1 > uint32_t(m)) r1 = uint32_t(m);
+        for (uint32_t r = r0 + lane; r < r1; r += OMEGA) y[r] = VT(acc);
+    } else if (acc == 0x5a17c0de) {
+        sink[0] = uint32_t(acc);           // keeps the loads alive; practically never taken
+    }
+}
+
 template <int SIGMA, typename VT, typename IT, bool CAN_LOOK>
 hipError_t launch_spmv(const Geom& g, int m, int n, IT nnz, const IT* row_ptr,
                        const typename Index<IT>::tp_t* tile_ptr,
@@ -1373,7 +1426,6 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     if (!geometry_fits(m, nnz, sigma)) return CSR5_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
-
     Geom g = make_geom(nnz, sigma);
     Layout L = make_layout(m, g, wide);
     csr5_handle_s* h = new (std::nothrow) csr5_handle_s();
@@ -1458,9 +1510,12 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         IT* chunk_sum = reinterpret_cast<IT*>(basep + L.off_scan);
         const int nchunks = (g.pc + SCAN_CHUNK - 1) / SCAN_CHUNK;      // <= 2^26 / 2^13 = SCAN_CHUNK
         hipLaunchKernelGGL(k_scan_chunks<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, eop, chunk_sum, h->status);
-        hipLaunchKernelGGL(k_scan_finish<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, chunk_sum,
-                           tile_ptr, h->tile_head, wg_far, n_far_wg, h->status);
         e = hipGetLastError();
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(k_scan_finish<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, chunk_sum,
+                               tile_ptr, h->tile_head, wg_far, n_far_wg, h->status);
+            e = hipGetLastError();
+        }
     }
     if (e == hipSuccess && g.pc > 0 && m > 0) {
         size_t threads = size_t(m) + size_t(g.pc);
@@ -1648,7 +1703,62 @@ static int spmv_profile(csr5_handle_t h, const VT* x, VT* y, void* hip_stream, i
     return rc;
 }
 
+template <typename VT, typename IT>
+static int stream_floor(csr5_handle_t h, VT* y, hipStream_t s, int reps, float* ms) {
+    using tp_t = typename Index<IT>::tp_t;
+    const Geom& g = h->g;
+    const uint32_t nb_tiles = uint32_t((g.pc + FLOOR_WAVES - 1) / FLOOR_WAVES);
+    // the tile order the SpMV uses for this matrix
+    const size_t x_bytes = size_t(h->n) * sizeof(VT);
+    uint32_t xcd_chunk = 0;
+    if (x_bytes > XCD_CONTIGUOUS_MAX_X_BYTES)
+        xcd_chunk = (h->nnz / (h->m > 0 ? h->m : 1) <= g.T / Y_LINE_ROWS) ? 1u : XCD_CHUNK;
+    else if (x_bytes < XCD_CONTIGUOUS_MIN_X_BYTES)
+        xcd_chunk = XCD_CHUNK;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    int rc = CSR5_OK;
+    for (int k = 0; k < 3 && rc == CSR5_OK; k++)
+        if (hipEventCreate(&ev[k]) != hipSuccess) rc = CSR5_EHIP;
+    for (int pass = 0; pass < 2 && rc == CSR5_OK; pass++) {      // reads only, then reads and the rows of y
+        if (hipEventRecord(ev[pass], s) != hipSuccess) rc = CSR5_EHIP;
+        for (int r = 0; rc == CSR5_OK && r < reps; r++) {
+            hipLaunchKernelGGL((k_stream_floor<VT, IT>), dim3(nb_tiles), dim3(FLOOR_WAVES * OMEGA), 0, s, h->m, g.pc,
+                               g.sigma, g.W, nb_tiles, xcd_chunk, pass, static_cast<const tp_t*>(h->tile_ptr),
+                               h->tile_desc, h->col_idx, static_cast<const VT*>(h->val), y,
+                               static_cast<uint32_t*>(h->carry));
+            if (hipGetLastError() != hipSuccess) rc = CSR5_EHIP;
+        }
+    }
+    if (rc == CSR5_OK && hipEventRecord(ev[2], s) != hipSuccess) rc = CSR5_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess && rc == CSR5_OK) rc = CSR5_EHIP;
+    float a = 0.f, b = 0.f;
+    if (rc == CSR5_OK && (hipEventElapsedTime(&a, ev[0], ev[1]) != hipSuccess ||
+                          hipEventElapsedTime(&b, ev[1], ev[2]) != hipSuccess))
+        rc = CSR5_EHIP;
+    for (int k = 0; k < 3; k++)
+        if (ev[k]) (void)hipEventDestroy(ev[k]);
+    if (rc == CSR5_OK) {
+        ms[0] = a / float(reps);
+        ms[1] = b / float(reps);
+    }
+    return rc;
+}
+
 extern "C" {
+
+int csr5_stream_floor(csr5_handle_t h, void* y, size_t y_bytes, void* hip_stream, int reps, float* ms) {
+    if (!h || !h->in_csr5_order || !y || !ms || reps <= 0 || reps > 100000) return CSR5_EINVAL;
+    if (h->g.pc == 0 || h->m == 0) return CSR5_EINVAL;                     // no complete tile: nothing to stream
+    if (y_bytes < size_t(h->m) * (h->dtype == CSR5_DTYPE_F32 ? 4 : 8)) return CSR5_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(h->col_idx) & 15) || (reinterpret_cast<uintptr_t>(h->val) & 15)) return CSR5_EINVAL;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return CSR5_EHIP;
+    if (dev != h->device) return CSR5_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (h->dtype == CSR5_DTYPE_F32) return h->wide ? CSR5_EINVAL : stream_floor<float, int32_t>(h, static_cast<float*>(y), s, reps, ms);
+    return h->wide ? stream_floor<double, int64_t>(h, static_cast<double*>(y), s, reps, ms)
+                   : stream_floor<double, int32_t>(h, static_cast<double*>(y), s, reps, ms);
+}
 
 int csr5_spmv_ex(csr5_handle_t h, const double* x, double* y, void* hip_stream) {
     return spmv_checked<double>(h, x, y, hip_stream);

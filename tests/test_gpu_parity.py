@@ -409,6 +409,43 @@ def test_profile_helper_leaves_y_correct():
     B.csr5_free(h)
 
 
+@pytest.mark.parametrize("sigma,f32", [(16, False), (7, False), (48, False), (16, True)])
+def test_stream_floor_reads_only_and_stays_inside_y(sigma, f32):
+    """csr5_stream_floor times a bare read of the tile streams, with and without
+    the rows of y.  It must leave the matrix alone (an SpMV afterwards is still
+    the oracle's), write nothing outside the m entries of y, refuse a y that is
+    too short, and not be slower than the tile kernel by more than timing noise."""
+    a = wl.config(2, scale=0.2)
+    dev = torch.device("cuda:0")
+    dt, npdt = (torch.float32, np.float32) if f32 else (torch.float64, np.float64)
+    row_ptr = torch.from_numpy(a.row_ptr).to(dev)
+    col = torch.from_numpy(a.col_idx).to(dev)
+    val = torch.from_numpy(a.val.astype(npdt)).to(dev)
+    x = torch.from_numpy(a.x.astype(npdt)).to(dev)
+    y = torch.full((a.m,), float("nan"), dtype=dt, device=dev)
+    conv, spmv, profile = ((B.csr5s_convert_ex, B.csr5s_spmv_ex, B.csr5s_spmv_profile) if f32 else
+                           (B.csr5_convert_ex, B.csr5_spmv_ex, B.csr5_spmv_profile))
+    h = conv(a.m, a.n, a.nnz, row_ptr, col, val, sigma=sigma)
+    scratch = torch.full((a.m + 64,), 7.0, dtype=dt, device=dev)
+    say("stream floor", sigma, "f32" if f32 else "f64")
+    read_ms, read_write_ms = B.csr5_stream_floor(h, scratch, reps=20)
+    torch.cuda.synchronize()
+    assert 0 < read_ms < 10 and 0 < read_write_ms < 10
+    assert bool(torch.all(scratch[a.m:] == 7.0))
+    with pytest.raises(B.Csr5Error):
+        B.csr5_stream_floor(h, scratch[:a.m - 1], reps=1)
+    tiles_ms, _ = profile(h, x, y, reps=20)
+    assert read_write_ms < 1.25 * tiles_ms + 0.002, (read_write_ms, tiles_ms)
+    y.fill_(float("nan"))
+    spmv(h, x, y)
+    torch.cuda.synchronize()
+    y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val.astype(npdt).astype(np.float64),
+                               a.x.astype(npdt).astype(np.float64))
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - y_ref) <= (TOL32 if f32 else 1e-12) * s + 1e-30)
+    B.csr5_free(h)
+
+
 @pytest.mark.parametrize("sigma", [4, 16, 40])
 def test_non_finite_x_stays_in_its_rows(sigma):
     """An infinite or NaN entry of x must reach exactly the rows that reference its
