@@ -839,6 +839,7 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     // one slot per tile entry: a column index on the way in, an x value on the way back,
     // a segment sum at the end (so single precision needs half the space)
     __shared__ VT lds[WAVES][OMEGA * PITCH];
+    __shared__ VT last_sum[WAVES];    // look-behind inside a workgroup: every tile's last segment, for the next tile
 
     const uint32_t st = *status;      // consulted below, after the streaming loads are in flight
     // Rows that cross a tile boundary are completed by look-behind in the whole
@@ -867,7 +868,11 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / OMEGA);
     const int tile = int(xcd_order(blockIdx.x - has_tail, nb_tiles, xcd_chunk)) * WAVES + wave;
-    if (tile >= pc) return;
+    // (every wavefront of a tile workgroup passes exactly one barrier, see below)
+    if (tile >= pc) {
+        if constexpr (CAN_LOOK) __syncthreads();
+        return;
+    }
 
     // ---- look-behind, first part: the previous tile's last LOOK entries, whether
     // or not this tile turns out to need them (asking first would put a dependent
@@ -875,10 +880,14 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     // them in turn).  Lanes LOOK.. repeat the addresses of lanes 0..LOOK-1.
     VT head_v = VT(0), head_x = VT(0);
     int32_t head_c = 0;
+    // Only the first tile of a workgroup needs them: the others get the finished
+    // sum of their row's head from the wavefront next door (last_sum).
     if constexpr (CAN_LOOK) {
-        const size_t rec = size_t(tile > 0 ? tile - 1 : 0);
-        head_c = last_col[rec * LAST_COL_STRIDE + size_t(lane & (LOOK - 1))];
-        head_v = last_val[rec * last_val_stride<VT>() + size_t(lane & (LOOK - 1))];
+        if (wave == 0) {
+            const size_t rec = size_t(tile > 0 ? tile - 1 : 0);
+            head_c = last_col[rec * LAST_COL_STRIDE + size_t(lane & (LOOK - 1))];
+            head_v = last_val[rec * last_val_stride<VT>() + size_t(lane & (LOOK - 1))];
+        }
     }
 
     // ---- stream the tile.  val: at step j the 64 lanes read 64 consecutive
@@ -937,7 +946,10 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         eo_t = eo + e0;
         nseg_t = uint32_t(e1 - e0);
     }
-    if ((st & BAD_BITS) || row0_wide >= tp_t(m)) return;  // rejected input: gather and store nothing
+    if ((st & BAD_BITS) || row0_wide >= tp_t(m)) {        // rejected input: gather and store nothing
+        if constexpr (CAN_LOOK) __syncthreads();
+        return;
+    }
     // Does segment 0 continue a row that an earlier tile opened?  (tile_head:
     // entries of the tile's first row that lie before the tile, saturated.)  Then
     // either this tile fetches the row's head (at most LOOK entries, see `look`)
@@ -948,7 +960,7 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     const uint32_t next_head = tile_head[tile + 1];           // p + 1 entries; 0 at p
     const bool cont0 = head_len != 0;
     const bool skip_last = look && next_head != 0;
-    const bool fetch_head = look && cont0 && head_len <= uint32_t(LOOK);   // uniform; the length test cannot fail
+    const bool fetch_head = look && cont0 && wave == 0 && head_len <= uint32_t(LOOK);   // uniform; the length test cannot fail
     // the head is the last head_len of those LOOK entries
     const bool head_lane = fetch_head && lane < LOOK && lane >= LOOK - int(head_len);
 
@@ -990,7 +1002,9 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         // spills into accumulator registers, one wavefront per SIMD).
         constexpr int GROUP = SIGMA > 46 ? 8 : (SIGMA > 32 ? 16 : SIGMA);
         // (without the look-behind the record holds nothing: the conversion did not fill it)
-        if constexpr (CAN_LOOK) head_x = x[look ? head_c : 0];
+        if constexpr (CAN_LOOK) {
+            if (wave == 0) head_x = x[look ? head_c : 0];
+        }
 #pragma unroll
         for (int k0 = 0; k0 < SIGMA; k0 += GROUP) {
 #pragma unroll
@@ -1049,8 +1063,19 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     if (dirty && nseg > nseg_t) nseg = nseg_t;            // cannot happen for a consistent format
     wave_sync_lds();
 
+    // The head of the tile's first row.  Tiles of one workgroup are neighbours: a
+    // tile's last segment, which the tile itself does not store when the row goes
+    // on (skip_last), is the head its successor needs, finished (in look-behind
+    // mode a row begins at most LOOK entries before a tile, so inside the previous
+    // one).  It crosses through LDS; the workgroup's first tile has no neighbour
+    // here and sums its head from the previous tile's record.
     VT head = VT(0);
-    if constexpr (CAN_LOOK) head = wave_sum(head_lane ? head_v * head_x : VT(0));
+    if constexpr (CAN_LOOK) {
+        if (lane == 0) last_sum[wave] = nseg ? yb[nseg - 1] : VT(0);     // (nseg >= 1: a tile's first flag is forced)
+        __syncthreads();
+        if (wave == 0) head = wave_sum(head_lane ? head_v * head_x : VT(0));
+        else if (look && cont0) head = last_sum[wave - 1];
+    }
 
     // ---- write the tile's rows.  Segment s is row tile_ptr + s, or
     // tile_ptr + empty_offset[s] when the tile holds empty rows.  Segment 0 goes
