@@ -271,8 +271,9 @@ def measure_on(P, sigma_arg, steps, warmup, headline, quick, stream):
         keep.append((rp_c, col_c, val_c, ws_c))
         rot.append((h_c, x_c, y_c))
     torch.cuda.synchronize()
-    warm_calls = [lambda: P.spmv_ex(h, P.x, y, stream=stream)]
-    rot_calls = [(lambda t=t: P.spmv_ex(t[0], t[1], t[2], stream=stream)) for t in rot]
+    # (arguments checked and marshalled once: the loops below only make the C call)
+    warm_calls = [B.csr5_spmv_bound(h, P.x, y, stream=stream)]
+    rot_calls = [B.csr5_spmv_bound(t[0], t[1], t[2], stream=stream) for t in rot]
 
     # ---------------------------------------------------------------- dominant kernel, HIP events inside the library
     # These series come first on purpose.  After even a short idle spell the chip

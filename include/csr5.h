@@ -83,9 +83,10 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * (p_c*W*64 words) + empty_offset_ptr (p_c+1 words) + empty_offset (at most
  * min(m + p_c, p_c*T) words) + the SpMV's four auxiliary arrays (p+1 doubles each) + one
  * word per tile saying how far into its first row the tile starts (p+1) + for
- * 8 <= sigma <= 32 a copy of every complete tile's last 32 (col_idx, val) pairs in CSR
- * order (384 bytes per tile; it lets a tile finish a row that began in the
- * previous tile without a second kernel) + the conversion's scratch
+ * 8 <= sigma <= 32 a copy of the last 32 (col_idx, val) pairs in CSR order of every
+ * 4th complete tile (every 2nd for sigma > 16) and of the last one (384 bytes each;
+ * it lets a tile finish a row that began in the previous tile without a second
+ * kernel) + the conversion's scratch
  * (p_c/8192 + 1 + 8192 words) + a status word, each rounded up to 256 bytes.
  * Returns 0 for invalid arguments.
  */

@@ -272,6 +272,23 @@ def csr5_spmv_ex(h, x, y, stream=None, check=True):
     return _chk(load().csr5_spmv_ex(h, *_xy(h, x, y, "f64"), _stream(stream)), "csr5_spmv_ex", check)
 
 
+def csr5_spmv_bound(h, x, y, stream=None):
+    """csr5_spmv_ex (csr5s_spmv_ex for float32 tensors) with its arguments checked
+    and marshalled once: returns a function of no arguments that makes the call,
+    for loops that repeat one SpMV.  The tensors must stay alive and in place."""
+    import torch
+    f32 = not isinstance(x, int) and x is not None and x.dtype is torch.float32
+    fn = load().csr5s_spmv_ex if f32 else load().csr5_spmv_ex
+    where = "csr5s_spmv_ex" if f32 else "csr5_spmv_ex"
+    args = (h,) + _xy(h, x, y, "f32" if f32 else "f64") + (_stream(stream),)
+
+    def call():
+        rc = fn(*args)
+        if rc != CSR5_OK:
+            raise Csr5Error(rc, where)
+    return call
+
+
 def csr5_spmv_static(h, x, y, stream=None, check=True):
     """csr5_spmv_ex without any allocation: the cross-tile array is the library's static one."""
     return _chk(load().csr5_spmv_static(h, *_xy(h, x, y, "f64"), _stream(stream)), "csr5_spmv_static", check)

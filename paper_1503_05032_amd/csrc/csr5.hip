@@ -28,21 +28,29 @@ constexpr uint32_t STATUS_SCAN_NEEDED = 1u << 16;
 // LOOK entries into a row, so the SpMV needs its second kernel (see k_spmv).
 constexpr uint32_t STATUS_NEEDS_CARRY = 1u << 17;
 // A tile whose first segment continues a row that began at most LOOK entries
-// before the tile fetches those entries itself, from a copy of every tile's last
-// LOOK entries that the conversion keeps in CSR order next to the format (in the
-// transposed tile they are spread over sigma cache lines each for val and
-// col_idx; re-reading them there cost 16 % more memory traffic).  LOOK = 32 is
-// three cache lines per tile, read by every tile without first asking how long
-// its head is (a dependent load at that point costs more than the lines); 384
-// bytes per tile, not kept for sigma < LOOK_MIN_SIGMA, where it would be a large
-// part of the matrix, nor for sigma > LOOK_MAX_SIGMA, where the tile kernel has
-// no registers to spare (those matrices always take the auxiliary-array path).
+// before the tile completes that row itself.  The tiles of one workgroup of the
+// tile kernel are neighbours and hand the finished head over through LDS; the
+// first tile of a workgroup fetches the entries itself, from a copy of the last
+// LOOK entries of the tile before it that the conversion keeps in CSR order next
+// to the format (in the transposed tile they are spread over sigma cache lines
+// each for val and col_idx; re-reading them there cost 16 % more memory
+// traffic).  LOOK = 32 is three cache lines, read without first asking how long
+// the head is (a dependent load at that point costs more than the lines).  One
+// 384-byte record per workgroup of tiles (tile_group_waves), none for
+// sigma < LOOK_MIN_SIGMA, where the matrices are small, nor for
+// sigma > LOOK_MAX_SIGMA, where the tile kernel has no registers to spare (those
+// matrices always take the auxiliary-array path).
 constexpr int LOOK = 32;
 constexpr int LOOK_MIN_SIGMA = 8, LOOK_MAX_SIGMA = 32;
 constexpr bool look_sigma(int sigma) { return sigma >= LOOK_MIN_SIGMA && sigma <= LOOK_MAX_SIGMA; }
-// One record per tile: LOOK values (8 bytes each, 4 used in single precision)
-// followed by LOOK column indices, contiguous, so that a tile fetches it with one
-// run of three cache lines.  Strides of the two views of the record array:
+// Tiles (= wavefronts) per workgroup of the tile kernel and of the transposition,
+// chosen so the LDS buffer stays under 40 KB.
+constexpr int tile_group_waves(int sigma) { return sigma <= 16 ? 4 : (sigma <= 32 ? 2 : 1); }
+// One record per group of tiles, holding the last entries of the group's last
+// tile (of the last complete tile, for the last group): LOOK values (8 bytes each,
+// 4 used in single precision) followed by LOOK column indices, contiguous, so
+// that a tile fetches it with one run of three cache lines.  Record of tile t:
+// number t / tile_group_waves.  Strides of the two views of the record array:
 constexpr int LAST_REC_BYTES = LOOK * 8 + LOOK * 4;
 constexpr int LAST_COL_STRIDE = LAST_REC_BYTES / 4;           // in int32
 template <typename VT> constexpr int last_val_stride() { return LAST_REC_BYTES / int(sizeof(VT)); }
@@ -551,13 +559,12 @@ k_empty_offset(int m, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
 // lane happens to write exactly the addresses it read.  LDS rows are padded to
 // an odd pitch to avoid bank conflicts on the strided LDS read.  BACK = the
 // inverse permutation (CSR5 -> CSR, Section 3.6).  The last block also checks
-// the column indices of the incomplete tile.  The forward pass also keeps a copy
-// of every tile's last LOOK entries in CSR order when asked to.
+// the column indices of the incomplete tile.  The forward pass also keeps, per
+// workgroup, a copy of its last tile's last LOOK entries in CSR order when asked to.
 // ----------------------------------------------------------------------------
 template <int SIGMA>
 struct TransposeShape {
-    // tiles (= wavefronts) per workgroup, chosen so the LDS buffer stays under 40 KB
-    static constexpr int WAVES = SIGMA <= 16 ? 4 : (SIGMA <= 32 ? 2 : 1);
+    static constexpr int WAVES = tile_group_waves(SIGMA);
     static constexpr int PITCH = SIGMA | 1;
 };
 
@@ -586,7 +593,11 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
     bool bad = false;
     // The copy of the tile's last entries is for the SpMV's look-behind, which a
     // matrix with a tile far into a row never uses (the scan kernel has said so by now).
-    const bool keep_last = !BACK && last_val && last_col && !(*status & STATUS_NEEDS_CARRY);
+    // Only a group's last tile is looked at from outside its workgroup; the last
+    // complete tile also by the workgroup of the incomplete one.
+    const bool keep_last = !BACK && last_val && last_col && !(*status & STATUS_NEEDS_CARRY) &&
+                           (wave == WAVES - 1 || tile == pc - 1);
+    const size_t rec = size_t(tile) / WAVES;
 
     // ---- val: HBM -> registers -> LDS -> registers -> HBM
     VT v[SIGMA];
@@ -594,7 +605,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
 #pragma unroll
         for (int k = 0; k < SIGMA; k++) v[k] = __builtin_nontemporal_load(&val[base + k * OMEGA + lane]);
         // the tile's last LOOK entries, still in CSR order, for the SpMV's look-behind
-        if (!BACK && keep_last && lane >= OMEGA - LOOK) last_val[size_t(tile) * last_val_stride<VT>() + (lane - (OMEGA - LOOK))] = v[SIGMA - 1];
+        if (!BACK && keep_last && lane >= OMEGA - LOOK) last_val[rec * last_val_stride<VT>() + (lane - (OMEGA - LOOK))] = v[SIGMA - 1];
         if (!BACK) {
 #pragma unroll
             for (int k = 0; k < SIGMA; k++) {
@@ -630,7 +641,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
             c[k] = __builtin_nontemporal_load(&col_idx[base + k * OMEGA + lane]);
             bad |= (c[k] < 0) | (c[k] >= n);
         }
-        if (!BACK && keep_last && lane >= OMEGA - LOOK) last_col[size_t(tile) * LAST_COL_STRIDE + (lane - (OMEGA - LOOK))] = c[SIGMA - 1];
+        if (!BACK && keep_last && lane >= OMEGA - LOOK) last_col[rec * LAST_COL_STRIDE + (lane - (OMEGA - LOOK))] = c[SIGMA - 1];
         if (!BACK) {
 #pragma unroll
             for (int k = 0; k < SIGMA; k++) {
@@ -693,11 +704,14 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
 // row_ptr[tile_ptr] != tile*T).  Two ways, chosen per MATRIX during conversion
 // (status word), so that both tiles at a boundary decide alike without talking
 // to each other:
-//  * no tile starts more than LOOK = 32 entries into a row: every tile reads the
-//    head of its first row itself (at most 32 entries of the previous tile, from
-//    a CSR-order copy of each tile's last 32 entries; one extra gather), adds it
-//    to its segment 0 and stores the finished row; the previous tile does not
-//    store its last segment.  Such a matrix needs no second kernel at all.
+//  * no tile starts more than LOOK = 32 entries into a row: every tile adds the
+//    head of its first row to its segment 0 and stores the finished row; the
+//    previous tile does not store its last segment.  That segment IS the head,
+//    and inside a workgroup (four neighbouring tiles up to sigma = 16, two up to
+//    32) it is handed over through LDS behind one barrier; the workgroup's first
+//    tile sums the head itself (at most 32 entries of the previous tile, from a
+//    CSR-order copy of the last 32 entries of every workgroup's last tile; one
+//    extra gather).  Such a matrix needs no second kernel at all.
 //  * otherwise: the auxiliary array.  Segment 0 goes to carry[tile]; the tile that
 //    holds the row's first nonzero stores the row's base value, and k_spmv_fixup
 //    adds the carries afterwards.
@@ -853,8 +867,8 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         const tp_t first_row = tile_ptr[pc] & Index<IT>::ROWMASK;
         spmv_tail<VT, IT>(m, nnz, IT(pc) * T, first_row > tp_t(m) ? uint32_t(m) : uint32_t(first_row),
                           row_ptr, col_idx, val, x, y, carry + pc,
-                          (look && pc > 0) ? last_col + size_t(pc - 1) * LAST_COL_STRIDE : nullptr,
-                          (look && pc > 0) ? last_val + size_t(pc - 1) * last_val_stride<VT>() : nullptr);
+                          (look && pc > 0) ? last_col + size_t((pc - 1) / WAVES) * LAST_COL_STRIDE : nullptr,
+                          (look && pc > 0) ? last_val + size_t((pc - 1) / WAVES) * last_val_stride<VT>() : nullptr);
         return;
     }
     if (blockIdx.x >= has_tail + nb_tiles) {   // workgroups after the tiles: the zeros of rows without nonzeros
@@ -884,7 +898,7 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     // sum of their row's head from the wavefront next door (last_sum).
     if constexpr (CAN_LOOK) {
         if (wave == 0) {
-            const size_t rec = size_t(tile > 0 ? tile - 1 : 0);
+            const size_t rec = size_t(tile > 0 ? tile - 1 : 0) / WAVES;      // the group before this one
             head_c = last_col[rec * LAST_COL_STRIDE + size_t(lane & (LOOK - 1))];
             head_v = last_val[rec * last_val_stride<VT>() + size_t(lane & (LOOK - 1))];
         }
@@ -1334,8 +1348,8 @@ struct csr5_handle_s {
     size_t carry_slot_bytes;
     std::atomic<uint32_t> carry_turn;
     uint32_t* tile_head;   // per tile: entries of its first row that lie before it, saturated at LOOK + 1
-    // CSR-order copy of every complete tile's last LOOK entries (NULL for small sigma):
-    // two views of one array of LAST_REC_BYTES-byte records
+    // CSR-order copy of the last LOOK entries of every tile group's last tile (NULL for
+    // small and for large sigma): two views of one array of LAST_REC_BYTES-byte records
     int32_t* last_col;
     void* last_val;
     void* owned;           // hipMalloc'ed block, or NULL when a workspace was given
@@ -1371,7 +1385,8 @@ Layout make_layout(int32_t m, const Geom& g, bool wide) {
     L.carry_slot_bytes = align256((size_t(g.p) + 1) * 8);
     L.off_carry = o;    o += L.carry_slot_bytes * CARRY_SLOTS;
     L.has_last = look_sigma(g.sigma) && g.pc > 0;
-    L.off_last = o;     o += L.has_last ? align256(size_t(g.pc) * LAST_REC_BYTES) : 0;
+    const size_t groups = (size_t(g.pc) + tile_group_waves(g.sigma) - 1) / tile_group_waves(g.sigma);
+    L.off_last = o;     o += L.has_last ? align256(groups * LAST_REC_BYTES) : 0;
     L.off_scan = o;     o += align256((size_t(g.pc) / SCAN_CHUNK + 1) * isz);   // chunk totals of the scan
     L.off_wg_far = o;   o += align256(size_t(MAX_TILE_PTR_WG) * 4);              // one word per workgroup of k_tile_ptr
     L.off_status = o;   o += 256;

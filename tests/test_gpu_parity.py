@@ -409,6 +409,35 @@ def test_profile_helper_leaves_y_correct():
     B.csr5_free(h)
 
 
+@pytest.mark.parametrize("f32", [False, True])
+def test_bound_call_is_the_same_call(f32):
+    """binding.csr5_spmv_bound marshals once and then only makes the C call: the
+    result is csr5_spmv_ex's, bit for bit, on a matrix without atomics in its sums."""
+    a = wl.config(2, scale=0.05)
+    dev = torch.device("cuda:0")
+    dt, npdt = (torch.float32, np.float32) if f32 else (torch.float64, np.float64)
+    row_ptr = torch.from_numpy(a.row_ptr).to(dev)
+    col = torch.from_numpy(a.col_idx).to(dev)
+    val = torch.from_numpy(a.val.astype(npdt)).to(dev)
+    x = torch.from_numpy(a.x.astype(npdt)).to(dev)
+    y1 = torch.full((a.m,), float("nan"), dtype=dt, device=dev)
+    y2 = torch.full((a.m,), float("nan"), dtype=dt, device=dev)
+    conv, spmv = (B.csr5s_convert_ex, B.csr5s_spmv_ex) if f32 else (B.csr5_convert_ex, B.csr5_spmv_ex)
+    h = conv(a.m, a.n, a.nnz, row_ptr, col, val)
+    spmv(h, x, y1)
+    call = B.csr5_spmv_bound(h, x, y2)
+    call()
+    call()
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+    y_ref, s = oracle.csr_spmv(a.m, a.row_ptr, a.col_idx, a.val.astype(npdt).astype(np.float64),
+                               a.x.astype(npdt).astype(np.float64))
+    assert np.all(np.abs(y2.cpu().numpy().astype(np.float64) - y_ref) <= (TOL32 if f32 else 1e-12) * s + 1e-30)
+    with pytest.raises(ValueError):
+        B.csr5_spmv_bound(h, x, y2[:a.m - 1])
+    B.csr5_free(h)
+
+
 @pytest.mark.parametrize("sigma,f32", [(16, False), (7, False), (48, False), (16, True)])
 def test_stream_floor_reads_only_and_stays_inside_y(sigma, f32):
     """csr5_stream_floor times a bare read of the tile streams, with and without
