@@ -138,7 +138,8 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, i
  * complete tile by a row-wise SIMD reduction).  A tile's first segment, when it
  * continues a row of an earlier tile, is completed in one of two ways, fixed per
  * matrix at conversion: if no tile starts more than 32 entries into a row
- * (and 8 <= sigma <= 32), every tile re-reads the head of its first row and stores the
+ * (and 8 <= sigma <= 32), every tile adds the head of its first row itself (handed
+ * over by the neighbouring tile of its workgroup, or re-read) and stores the
  * finished row, and the SpMV is ONE kernel; otherwise those segments go through
  * an auxiliary array that a second small kernel adds to y (Section 4's "global
  * auxiliary array").  Which of the two, and whether rows without nonzeros need
