@@ -83,8 +83,8 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * (p_c*W*64 words) + empty_offset_ptr (p_c+1 words) + empty_offset (at most
  * min(m + p_c, p_c*T) words) + the SpMV's four auxiliary arrays (p+1 doubles each) + one
  * word per tile saying how far into its first row the tile starts (p+1) + for
- * 8 <= sigma <= 32 a copy of the last 32 (col_idx, val) pairs in CSR order of every
- * 4th complete tile (every 2nd for sigma > 16) and of the last one (384 bytes each;
+ * 8 <= sigma <= 32 a copy of the last 160 (col_idx, val) pairs in CSR order of every
+ * 4th complete tile (every 2nd for sigma > 16) and of the last one (1920 bytes each;
  * it lets a tile finish a row that began in the previous tile without a second
  * kernel) + the conversion's scratch
  * (p_c/8192 + 1 + 8192 words) + a status word, each rounded up to 256 bytes.
@@ -137,10 +137,12 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, i
  * y = A*x (Section 4: Algorithm 8 per complete tile; the entries after the last
  * complete tile by a row-wise SIMD reduction).  A tile's first segment, when it
  * continues a row of an earlier tile, is completed in one of two ways, fixed per
- * matrix at conversion: if no tile starts more than 32 entries into a row
- * (and 8 <= sigma <= 32), every tile adds the head of its first row itself (handed
- * over by the neighbouring tile of its workgroup, or re-read) and stores the
- * finished row, and the SpMV is ONE kernel; otherwise those segments go through
+ * matrix at conversion: if every tile can get at the head of its first row
+ * (8 <= sigma <= 32; every 4th tile, every 2nd for sigma > 16, starts at most 160
+ * entries into a row and re-reads them, the others start at most a tile's length
+ * into a row and are handed the sum by the neighbouring tile of their
+ * workgroup; in particular every matrix without a row longer than 161), it adds
+ * the head itself and stores the finished row, and the SpMV is ONE kernel; otherwise those segments go through
  * an auxiliary array that a second small kernel adds to y (Section 4's "global
  * auxiliary array").  Which of the two, and whether rows without nonzeros need
  * their zeros written, is in the conversion's status word: the library launches

@@ -24,36 +24,48 @@ constexpr uint32_t BAD_BITS = CSR5_STATUS_BAD_ROW_PTR | CSR5_STATUS_BAD_COL_IDX;
 // empty_offset layout has to be scanned.  Set by k_tile_desc only; the scan
 // kernels decide on it, and nothing in their own launches changes it.
 constexpr uint32_t STATUS_SCAN_NEEDED = 1u << 16;
-// Internal status bit: some tile (the incomplete one included) starts more than
-// LOOK entries into a row, so the SpMV needs its second kernel (see k_spmv).
+// Internal status bit: some tile (the incomplete one included) starts further
+// into a row than the tile kernel can make up for on its own, so the SpMV needs
+// its second kernel (see k_spmv and k_tile_ptr).
 constexpr uint32_t STATUS_NEEDS_CARRY = 1u << 17;
-// A tile whose first segment continues a row that began at most LOOK entries
-// before the tile completes that row itself.  The tiles of one workgroup of the
-// tile kernel are neighbours and hand the finished head over through LDS; the
-// first tile of a workgroup fetches the entries itself, from a copy of the last
-// LOOK entries of the tile before it that the conversion keeps in CSR order next
-// to the format (in the transposed tile they are spread over sigma cache lines
-// each for val and col_idx; re-reading them there cost 16 % more memory
-// traffic).  LOOK = 32 is three cache lines, read without first asking how long
-// the head is (a dependent load at that point costs more than the lines).  One
-// 384-byte record per workgroup of tiles (tile_group_waves), none for
+// A tile whose first segment continues a row of the previous tile completes
+// that row itself when it can get at the row's head.  The tiles of one
+// workgroup of the tile kernel are neighbours and hand the finished head over
+// through LDS (any head that began inside the previous tile).  The first tile of
+// a workgroup sums the head itself, from a copy of the last LOOK_MAX entries of
+// the tile before it that the conversion keeps in CSR order next to the format
+// (in the transposed tile they are spread over sigma cache lines each for val
+// and col_idx; re-reading them there cost 16 % more memory traffic).  The last
+// LOOK = 32 of them are three cache lines, read without first asking how long
+// the head is (a dependent load at that point costs more than the lines); the
+// LOOK_FAR = 128 before them are read only by a tile whose head is longer than
+// LOOK.  One record per workgroup of tiles (tile_group_waves), none for
 // sigma < LOOK_MIN_SIGMA, where the matrices are small, nor for
 // sigma > LOOK_MAX_SIGMA, where the tile kernel has no registers to spare (those
 // matrices always take the auxiliary-array path).
 constexpr int LOOK = 32;
+constexpr int LOOK_FAR = 128;
+constexpr int LOOK_MAX = LOOK + LOOK_FAR;
 constexpr int LOOK_MIN_SIGMA = 8, LOOK_MAX_SIGMA = 32;
 constexpr bool look_sigma(int sigma) { return sigma >= LOOK_MIN_SIGMA && sigma <= LOOK_MAX_SIGMA; }
 // Tiles (= wavefronts) per workgroup of the tile kernel and of the transposition,
 // chosen so the LDS buffer stays under 40 KB.
 constexpr int tile_group_waves(int sigma) { return sigma <= 16 ? 4 : (sigma <= 32 ? 2 : 1); }
-// One record per group of tiles, holding the last entries of the group's last
-// tile (of the last complete tile, for the last group): LOOK values (8 bytes each,
-// 4 used in single precision) followed by LOOK column indices, contiguous, so
-// that a tile fetches it with one run of three cache lines.  Record of tile t:
-// number t / tile_group_waves.  Strides of the two views of the record array:
-constexpr int LAST_REC_BYTES = LOOK * 8 + LOOK * 4;
+// One record per group of tiles, holding the last LOOK_MAX entries, in CSR
+// order, of the group's last tile (of the last complete tile, for the last
+// group).  Near part first: LOOK values (8 bytes each, 4 used in single
+// precision) followed by LOOK column indices, contiguous, so that a tile fetches
+// it with one run of three cache lines; then the far part, LOOK_FAR values and
+// LOOK_FAR column indices (entry j of the far part is entry T - LOOK_MAX + j of
+// the tile, entry i of the near part entry T - LOOK + i).  Record of tile t:
+// number t / tile_group_waves.  Strides of the two views of the record array
+// (last_val points at a record's first byte, last_col at its near indices):
+constexpr int LAST_REC_BYTES = LOOK_MAX * 8 + LOOK_MAX * 4;
 constexpr int LAST_COL_STRIDE = LAST_REC_BYTES / 4;           // in int32
 template <typename VT> constexpr int last_val_stride() { return LAST_REC_BYTES / int(sizeof(VT)); }
+// where a record's far part begins, counted from last_val / last_col of the record
+template <typename VT> constexpr int far_val_at() { return (LOOK * 8 + LOOK * 4) / int(sizeof(VT)); }
+constexpr int FAR_COL_AT = (LOOK * 8 + LOOK * 4 + LOOK_FAR * 8 - LOOK * 8) / 4;
 constexpr uint32_t STATUS_PUBLIC = 0xffu;
 constexpr int NUM_XCD = 8;  // MI355X: 8 accelerator dies, each with its own L2
 
@@ -186,7 +198,7 @@ __device__ __forceinline__ uint32_t xcd_order(uint32_t w, uint32_t nb, uint32_t 
 // ----------------------------------------------------------------------------
 template <typename IT>
 __global__ void __launch_bounds__(256)
-k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p,
+k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p, int pc, int group,
            typename Index<IT>::tp_t* __restrict__ tile_ptr, uint32_t* __restrict__ tile_head,
            uint32_t* __restrict__ wg_far, uint32_t* __restrict__ desc, size_t ndesc,
            uint32_t* __restrict__ status) {
@@ -201,14 +213,20 @@ k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p,
         const int row = count_le(row_ptr, m + 1, bnd) - 1;
         tile_ptr[t] = tp_t(row) & Index<IT>::ROWMASK;
         // how far into its first row the tile starts (0: the row starts with the
-        // tile), saturated at LOOK + 1: what the SpMV needs to know about the
+        // tile), saturated at 32 bits: what the SpMV needs to know about the
         // boundary, so that it does not have to look into row_ptr itself
         int64_t head = 0;
         if (t < size_t(p) && row >= 0 && row < m) head = bnd - int64_t(row_ptr[row]);
-        tile_head[t] = uint32_t(head < 0 ? 0 : (head > LOOK + 1 ? LOOK + 1 : head));
-        far |= int(head > LOOK);
+        tile_head[t] = uint32_t(head < 0 ? 0 : (head > int64_t(0xffffffffu) ? int64_t(0xffffffffu) : head));
+        // Can the tile kernel complete that row on its own?  The first tile of a
+        // workgroup (and the workgroup of the incomplete tile) re-reads the head
+        // from the previous tile's record: at most LOOK_MAX entries.  The other
+        // tiles are handed their neighbour's last segment, which is the whole
+        // head if the row began inside (or with) that neighbour: at most T entries.
+        const bool from_record = (t % size_t(group)) == 0 || t >= size_t(pc);
+        far |= int(head > (from_record ? int64_t(LOOK_MAX) : int64_t(T)));
     }
-    // "Some tile starts more than LOOK entries into a row" (the SpMV then needs its
+    // "Some tile starts too far into a row" (the SpMV then needs its
     // carry array) does not go to the status word from here -- this launch also
     // clears that word, and thousands of workgroups saying so would queue at it --
     // but into one word per workgroup, which the scan kernel collects.
@@ -604,8 +622,21 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
     if (active) {
 #pragma unroll
         for (int k = 0; k < SIGMA; k++) v[k] = __builtin_nontemporal_load(&val[base + k * OMEGA + lane]);
-        // the tile's last LOOK entries, still in CSR order, for the SpMV's look-behind
-        if (!BACK && keep_last && lane >= OMEGA - LOOK) last_val[rec * last_val_stride<VT>() + (lane - (OMEGA - LOOK))] = v[SIGMA - 1];
+        // the tile's last LOOK_MAX entries, still in CSR order (entry k*64 + lane of
+        // the tile is v[k] here), for the SpMV's look-behind: near part, far part
+        if constexpr (!BACK && look_sigma(SIGMA)) {
+            if (keep_last) {
+                VT* const near_v = last_val + rec * last_val_stride<VT>();
+                VT* const far_v = near_v + far_val_at<VT>();
+                if (lane >= OMEGA - LOOK) {
+                    near_v[lane - (OMEGA - LOOK)] = v[SIGMA - 1];
+                    far_v[lane - (OMEGA - LOOK)] = v[SIGMA - 3];
+                } else {
+                    far_v[LOOK_FAR - LOOK + lane] = v[SIGMA - 1];
+                }
+                far_v[LOOK + lane] = v[SIGMA - 2];
+            }
+        }
         if (!BACK) {
 #pragma unroll
             for (int k = 0; k < SIGMA; k++) {
@@ -641,7 +672,19 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
             c[k] = __builtin_nontemporal_load(&col_idx[base + k * OMEGA + lane]);
             bad |= (c[k] < 0) | (c[k] >= n);
         }
-        if (!BACK && keep_last && lane >= OMEGA - LOOK) last_col[rec * LAST_COL_STRIDE + (lane - (OMEGA - LOOK))] = c[SIGMA - 1];
+        if constexpr (!BACK && look_sigma(SIGMA)) {
+            if (keep_last) {
+                int32_t* const near_c = last_col + rec * LAST_COL_STRIDE;
+                int32_t* const far_c = near_c + FAR_COL_AT;
+                if (lane >= OMEGA - LOOK) {
+                    near_c[lane - (OMEGA - LOOK)] = c[SIGMA - 1];
+                    far_c[lane - (OMEGA - LOOK)] = c[SIGMA - 3];
+                } else {
+                    far_c[LOOK_FAR - LOOK + lane] = c[SIGMA - 1];
+                }
+                far_c[LOOK + lane] = c[SIGMA - 2];
+            }
+        }
         if (!BACK) {
 #pragma unroll
             for (int k = 0; k < SIGMA; k++) {
@@ -704,14 +747,16 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
 // row_ptr[tile_ptr] != tile*T).  Two ways, chosen per MATRIX during conversion
 // (status word), so that both tiles at a boundary decide alike without talking
 // to each other:
-//  * no tile starts more than LOOK = 32 entries into a row: every tile adds the
-//    head of its first row to its segment 0 and stores the finished row; the
-//    previous tile does not store its last segment.  That segment IS the head,
-//    and inside a workgroup (four neighbouring tiles up to sigma = 16, two up to
-//    32) it is handed over through LDS behind one barrier; the workgroup's first
-//    tile sums the head itself (at most 32 entries of the previous tile, from a
-//    CSR-order copy of the last 32 entries of every workgroup's last tile; one
-//    extra gather).  Such a matrix needs no second kernel at all.
+//  * every tile can get at the head of its first row: it adds the head to its
+//    segment 0 and stores the finished row; the previous tile does not store its
+//    last segment.  That segment IS the head when the row began inside the
+//    previous tile, and inside a workgroup (four neighbouring tiles up to
+//    sigma = 16, two up to 32) it is handed over through LDS behind one barrier.
+//    The workgroup's first tile sums the head itself, from a CSR-order copy of the
+//    last LOOK_MAX = 160 entries of the previous workgroup's last tile (one extra
+//    gather for heads up to 32 entries, three beyond).  So the condition is: no
+//    first tile of a workgroup starts more than 160 entries into a row, and no
+//    other tile more than a tile's length.  Such a matrix needs no second kernel.
 //  * otherwise: the auxiliary array.  Segment 0 goes to carry[tile]; the tile that
 //    holds the row's first nonzero stores the row's base value, and k_spmv_fixup
 //    adds the carries afterwards.
@@ -738,18 +783,26 @@ __device__ __forceinline__ VT wave_sum(VT v) {
     return v;
 }
 
-// The last `count` (<= LOOK) entries of a complete tile, read from the CSR-order
-// copy of its last LOOK entries: lane k multiplies entry LOOK - count + k by its x
+// The last `count` (<= LOOK_MAX) entries of a complete tile, read from the
+// CSR-order record of its last entries (near part: the last LOOK; far part: the
+// LOOK_FAR before them): every lane multiplies up to three of them by their x
 // and the wavefront sums the products.  This is how the incomplete tile's
 // workgroup completes a row that began shortly before it, instead of handing its
-// part to a second kernel (the complete tiles do the same inside k_spmv).
+// part to a second kernel (the first tile of a workgroup does the same inside
+// k_spmv).  last_col, last_val: the record's two views.
 template <typename VT>
 __device__ __forceinline__ VT look_behind(const int32_t* __restrict__ last_col, const VT* __restrict__ last_val,
                                           const VT* __restrict__ x, int count, int lane) {
     VT prod = VT(0);
-    if (lane < count) {
-        const int at = LOOK - count + lane;
-        prod = last_val[at] * x[last_col[at]];
+    const int near_n = count < LOOK ? count : LOOK;
+    if (lane >= LOOK - near_n && lane < LOOK) prod = last_val[lane] * x[last_col[lane]];
+    if (count > LOOK) {                                   // uniform
+        const int32_t* const far_c = last_col + FAR_COL_AT;
+        const VT* const far_v = last_val + far_val_at<VT>();
+        const int first = LOOK_FAR - (count - LOOK);      // far entries first .. LOOK_FAR - 1 belong to the head
+#pragma unroll
+        for (int j = lane; j < LOOK_FAR; j += OMEGA)
+            if (j >= first) prod = fma(far_v[j], x[far_c[j]], prod);
     }
     return wave_sum(prod);
 }
@@ -823,7 +876,7 @@ __device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
         VT carried = acc_first;
         if (last_col && row_lo < m && first > 0) {       // last_col: entries of the last complete tile, or null
             const IT rs = row_ptr[row_lo];
-            if (rs < first && first - rs <= IT(LOOK)) {  // the first row began shortly before: finish it here
+            if (rs < first && first - rs <= IT(LOOK_MAX)) {  // the first row began shortly before: finish it here
                 const VT head = look_behind<VT>(last_col, last_val, x, int(first - rs), lane);
                 if (lane == 0) y[row_lo] = head + acc_first;
                 carried = VT(0);
@@ -888,19 +941,35 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         return;
     }
 
+    // How far into its first row the tile starts, and the next tile into its own
+    // (tile_head: entries of a tile's first row that lie before the tile; p + 1
+    // entries, 0 at p).  The same for every lane: scalar loads.
+    const uint32_t head_len = tile_head[tile];
+    const uint32_t next_head = tile_head[tile + 1];
+
     // ---- look-behind, first part: the previous tile's last LOOK entries, whether
     // or not this tile turns out to need them (asking first would put a dependent
     // load in front of these, and everything the wavefront loads later waits for
     // them in turn).  Lanes LOOK.. repeat the addresses of lanes 0..LOOK-1.
-    VT head_v = VT(0), head_x = VT(0);
-    int32_t head_c = 0;
     // Only the first tile of a workgroup needs them: the others get the finished
-    // sum of their row's head from the wavefront next door (last_sum).
+    // sum of their row's head from the wavefront next door (last_sum).  A head
+    // longer than LOOK also takes the far part of the record, two entries per lane.
+    VT head_v = VT(0), head_x = VT(0), far_v0 = VT(0), far_v1 = VT(0), far_prod = VT(0);
+    int32_t head_c = 0, far_c0 = 0, far_c1 = 0;
+    const bool far_head = CAN_LOOK && look && wave == 0 && head_len > uint32_t(LOOK);      // uniform
     if constexpr (CAN_LOOK) {
         if (wave == 0) {
             const size_t rec = size_t(tile > 0 ? tile - 1 : 0) / WAVES;      // the group before this one
-            head_c = last_col[rec * LAST_COL_STRIDE + size_t(lane & (LOOK - 1))];
-            head_v = last_val[rec * last_val_stride<VT>() + size_t(lane & (LOOK - 1))];
+            const int32_t* const near_c = last_col + rec * LAST_COL_STRIDE;
+            const VT* const near_v = last_val + rec * last_val_stride<VT>();
+            head_c = near_c[lane & (LOOK - 1)];
+            head_v = near_v[lane & (LOOK - 1)];
+            if (far_head) {
+                far_c0 = near_c[FAR_COL_AT + lane];
+                far_c1 = near_c[FAR_COL_AT + OMEGA + lane];
+                far_v0 = near_v[far_val_at<VT>() + lane];
+                far_v1 = near_v[far_val_at<VT>() + OMEGA + lane];
+            }
         }
     }
 
@@ -964,19 +1033,16 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         if constexpr (CAN_LOOK) __syncthreads();
         return;
     }
-    // Does segment 0 continue a row that an earlier tile opened?  (tile_head:
-    // entries of the tile's first row that lie before the tile, saturated.)  Then
-    // either this tile fetches the row's head (at most LOOK entries, see `look`)
-    // and stores the finished row, or its part goes through the carry array.
+    // Does segment 0 continue a row that an earlier tile opened?  Then either this
+    // tile gets hold of the row's head (see `look`) and stores the finished row,
+    // or its part goes through the carry array.
     // The mirror image: when the next tile (or the incomplete tile's workgroup)
     // completes this tile's last row, this tile must not store its part of it.
-    const uint32_t head_len = tile_head[tile];
-    const uint32_t next_head = tile_head[tile + 1];           // p + 1 entries; 0 at p
     const bool cont0 = head_len != 0;
     const bool skip_last = look && next_head != 0;
-    const bool fetch_head = look && cont0 && wave == 0 && head_len <= uint32_t(LOOK);   // uniform; the length test cannot fail
-    // the head is the last head_len of those LOOK entries
-    const bool head_lane = fetch_head && lane < LOOK && lane >= LOOK - int(head_len);
+    const bool fetch_head = look && cont0 && wave == 0;   // uniform; the head is then at most LOOK_MAX entries long
+    // the last min(head_len, LOOK) of the near LOOK entries belong to the head
+    const bool head_lane = fetch_head && lane < LOOK && lane >= LOOK - int(head_len < uint32_t(LOOK) ? head_len : uint32_t(LOOK));
 
     // ---- gather x.  Lane i owns the CSR entries i*sigma .. i*sigma+sigma-1 of the
     // tile, so at a fixed step the 64 lanes would gather from 64 unrelated
@@ -1016,8 +1082,15 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         // spills into accumulator registers, one wavefront per SIMD).
         constexpr int GROUP = SIGMA > 46 ? 8 : (SIGMA > 32 ? 16 : SIGMA);
         // (without the look-behind the record holds nothing: the conversion did not fill it)
+        VT far_x0 = VT(0), far_x1 = VT(0);
         if constexpr (CAN_LOOK) {
-            if (wave == 0) head_x = x[look ? head_c : 0];
+            if (wave == 0) {
+                head_x = x[look ? head_c : 0];
+                if (far_head) {
+                    far_x0 = x[far_c0];
+                    far_x1 = x[far_c1];
+                }
+            }
         }
 #pragma unroll
         for (int k0 = 0; k0 < SIGMA; k0 += GROUP) {
@@ -1033,6 +1106,13 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
 #pragma unroll
         for (int j = 0; j < SIGMA; j++) xv[j] = xb[lane * PITCH + j];
         wave_sync_lds();
+        if constexpr (CAN_LOOK) {
+            if (far_head) {     // far entries first .. LOOK_FAR - 1 belong to the head; lane holds entries lane and lane + 64
+                const int first = LOOK_FAR - int(head_len - uint32_t(LOOK));
+                if (lane >= first) far_prod = far_v0 * far_x0;
+                if (lane + OMEGA >= first) far_prod = fma(far_v1, far_x1, far_prod);
+            }
+        }
     }
 
     // ---- per-column walk.  Finished segment sums are parked in LDS (the buffer
@@ -1087,7 +1167,7 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     if constexpr (CAN_LOOK) {
         if (lane == 0) last_sum[wave] = nseg ? yb[nseg - 1] : VT(0);     // (nseg >= 1: a tile's first flag is forced)
         __syncthreads();
-        if (wave == 0) head = wave_sum(head_lane ? head_v * head_x : VT(0));
+        if (wave == 0) head = wave_sum(head_lane ? fma(head_v, head_x, far_prod) : far_prod);
         else if (look && cont0) head = last_sum[wave - 1];
     }
 
@@ -1347,7 +1427,7 @@ struct csr5_handle_s {
     void* carry;
     size_t carry_slot_bytes;
     std::atomic<uint32_t> carry_turn;
-    uint32_t* tile_head;   // per tile: entries of its first row that lie before it, saturated at LOOK + 1
+    uint32_t* tile_head;   // per tile: entries of its first row that lie before it, saturated at 32 bits
     // CSR-order copy of the last LOOK entries of every tile group's last tile (NULL for
     // small and for large sigma): two views of one array of LAST_REC_BYTES-byte records
     int32_t* last_col;
@@ -1526,8 +1606,8 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         size_t nb = (work + 255) / 256;
         if (nb > MAX_TILE_PTR_WG) nb = MAX_TILE_PTR_WG;
         n_far_wg = int(nb);
-        hipLaunchKernelGGL(k_tile_ptr<IT>, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p,
-                           tile_ptr, h->tile_head, wg_far, h->tile_desc, L.ndesc, h->status);
+        hipLaunchKernelGGL(k_tile_ptr<IT>, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p, g.pc,
+                           tile_group_waves(g.sigma), tile_ptr, h->tile_head, wg_far, h->tile_desc, L.ndesc, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && m > 0) {   // steps 2b + 3a

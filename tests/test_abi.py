@@ -58,7 +58,7 @@ def test_workspace_bytes(lib):
     p, pc = -(-nnz // T), nnz // T
     W = oracle.desc_words(64, sigma)
     need = (p + 1) * 4 + pc * W * 64 * 4 + (pc + 1) * 4 + min(m + pc, pc * T) * 4 + 4 * (p + 1) * 8 + 4
-    need += -(-pc // 4) * 32 * (4 + 8)     # copy of the last 32 entries of every 4th tile and of the last (8 <= sigma <= 16)
+    need += -(-pc // 4) * 160 * (4 + 8)    # copy of the last 160 entries of every 4th tile and of the last (8 <= sigma <= 16)
     need += (p + 1) * 4                    # per tile: how far into its first row it starts
     need += 8192 * 4                       # conversion scratch: one word per workgroup of the tile_ptr kernel
     got = B.csr5_workspace_bytes(m, nnz, sigma)
@@ -67,7 +67,7 @@ def test_workspace_bytes(lib):
     T24 = 64 * 24
     p24, pc24 = -(-nnz // T24), nnz // T24
     need24 = ((p24 + 1) * 4 + pc24 * oracle.desc_words(64, 24) * 64 * 4 + (pc24 + 1) * 4 + min(m + pc24, pc24 * T24) * 4
-              + 4 * (p24 + 1) * 8 + 4 + -(-pc24 // 2) * 32 * (4 + 8) + (p24 + 1) * 4 + 8192 * 4)
+              + 4 * (p24 + 1) * 8 + 4 + -(-pc24 // 2) * 160 * (4 + 8) + (p24 + 1) * 4 + 8192 * 4)
     assert need24 <= B.csr5_workspace_bytes(m, nnz, 24) <= need24 + 14 * 256
     # no such copy below sigma 8
     p4, pc4 = -(-nnz // 256), nnz // 256
@@ -92,7 +92,7 @@ def test_wide_variant_limits(lib):
     p, pc = -(-nnz // T), nnz // T
     W = oracle.desc_words(64, sigma)
     need = (p + 1) * 8 + pc * W * 64 * 4 + (pc + 1) * 8 + min(m + pc, pc * T) * 4 + 4 * (p + 1) * 8 + 4
-    need += -(-pc // 4) * 32 * (4 + 8) + (p + 1) * 4 + 8192 * 4
+    need += -(-pc // 4) * 160 * (4 + 8) + (p + 1) * 4 + 8192 * 4
     got = B.csr5l_workspace_bytes(m, nnz, sigma)
     assert need <= got <= need + 14 * 256
     # beyond 2^31 nonzeros; the limit is the number of tiles (2^26 - 5)

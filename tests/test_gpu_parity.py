@@ -409,6 +409,30 @@ def test_profile_helper_leaves_y_correct():
     B.csr5_free(h)
 
 
+@pytest.mark.parametrize("row_len,one_kernel", [(32, True), (33, True), (34, True), (96, True), (160, True), (161, True),
+                                                (163, False), (701, False)])
+def test_row_lengths_around_the_look_behind_limits(row_len, one_kernel):
+    """Every row has `row_len` entries, at three tile heights (workgroups of four
+    and of two tiles).  Up to 161 entries per row the SpMV is one kernel; with 163
+    (a prime, and more workgroups than that: every offset into a row occurs at a
+    workgroup's first tile) some such tile starts more than 160 entries into a row
+    and the second kernel is needed.
+    Either way y is the oracle's."""
+    m = 40_000 // row_len * 64 + 37
+    a = wl.from_row_lengths(np.full(m, row_len), 5 * row_len + 1000, seed=row_len, name=f"rows{row_len}")
+    for sigma in (8, 16, 24):
+        d = DeviceCsr(a)
+        h = convert(d, sigma=sigma)
+        say("row length", row_len, "sigma", sigma, a.m, a.nnz)
+        check_format(d, h, (a.name, sigma))
+        check_spmv(d, h, (a.name, sigma))
+        _, ms_second = B.csr5_spmv_profile(h, d.x, d.y, reps=50)
+        torch.cuda.synchronize()
+        assert (ms_second < 1e-3) == one_kernel, (row_len, sigma, ms_second)
+        _check_y(d.y.cpu().numpy()[:a.m], a, ("after profile", row_len, sigma))
+        B.csr5_free(h)
+
+
 @pytest.mark.parametrize("f32", [False, True])
 def test_bound_call_is_the_same_call(f32):
     """binding.csr5_spmv_bound marshals once and then only makes the C call: the
@@ -700,18 +724,19 @@ def test_one_handle_on_two_streams():
     B.csr5_free(h)
 
 
-@pytest.mark.parametrize("wide,seed", [(False, 31), (True, 32)])
-def test_random_short_row_matrices_take_one_kernel(wide, seed):
-    """Matrices whose rows have at most 33 entries, so that no tile can start more
-    than 32 entries into a row: for 8 <= sigma <= 32 their SpMV is the tile kernel
-    alone (the profile helper reports no second kernel), whatever the mix of empty
-    rows, and its result is the oracle's."""
+@pytest.mark.parametrize("wide,seed,longest", [(False, 31, 33), (True, 32, 33), (False, 33, 161), (True, 34, 161)])
+def test_random_short_row_matrices_take_one_kernel(wide, seed, longest):
+    """Matrices whose rows have at most 161 entries, so that no tile can start more
+    than 160 entries into a row (33 and 32: the part of the previous tile's record
+    that a workgroup's first tile always reads): for 8 <= sigma <= 32 their SpMV is
+    the tile kernel alone (the profile helper reports no second kernel), whatever
+    the mix of empty rows, and its result is the oracle's."""
     rng = np.random.default_rng(seed)
     for case in range(24):
         sigma = int(rng.integers(8, 33))
         m = int(rng.integers(200, 6000))
-        n = int(rng.integers(40, 8000))
-        top = int(rng.integers(1, 34))
+        n = int(rng.integers(40 if longest < 40 else 200, 8000))
+        top = int(rng.integers(1, longest + 1))
         lens = rng.integers(0, top + 1, size=m)
         if case % 3 == 0:
             lens *= rng.random(m) < 0.5                      # many empty rows
