@@ -139,10 +139,12 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, i
  * continues a row of an earlier tile, is completed in one of two ways, fixed per
  * matrix at conversion: if every tile can get at the head of its first row
  * (8 <= sigma <= 32; every 4th tile, every 2nd for sigma > 16, starts at most 160
- * entries into a row and re-reads them, the others start at most a tile's length
- * into a row and are handed the sum by the neighbouring tile of their
- * workgroup; in particular every matrix without a row longer than 161), it adds
- * the head itself and stores the finished row, and the SpMV is ONE kernel; otherwise those segments go through
+ * entries into a row -- 32 in a matrix of more than 28 million nonzeros -- and
+ * re-reads them, the others start at most a tile's length into a row and are
+ * handed the sum by the neighbouring tile of their workgroup; in particular
+ * every matrix without a row longer than 33, and up to 28 million nonzeros every
+ * matrix without a row longer than 161), it adds the head itself and stores the
+ * finished row, and the SpMV is ONE kernel; otherwise those segments go through
  * an auxiliary array that a second small kernel adds to y (Section 4's "global
  * auxiliary array").  Which of the two, and whether rows without nonzeros need
  * their zeros written, is in the conversion's status word: the library launches

@@ -28,6 +28,10 @@ constexpr uint32_t STATUS_SCAN_NEEDED = 1u << 16;
 // into a row than the tile kernel can make up for on its own, so the SpMV needs
 // its second kernel (see k_spmv and k_tile_ptr).
 constexpr uint32_t STATUS_NEEDS_CARRY = 1u << 17;
+// Internal status bit: some first tile of a workgroup (or the incomplete tile)
+// starts more than LOOK entries into a row: the look-behind of this matrix reads
+// the far part of the records too (see below).
+constexpr uint32_t STATUS_FAR_HEADS = 1u << 18;
 // A tile whose first segment continues a row of the previous tile completes
 // that row itself when it can get at the row's head.  The tiles of one
 // workgroup of the tile kernel are neighbours and hand the finished head over
@@ -46,6 +50,13 @@ constexpr uint32_t STATUS_NEEDS_CARRY = 1u << 17;
 constexpr int LOOK = 32;
 constexpr int LOOK_FAR = 128;
 constexpr int LOOK_MAX = LOOK + LOOK_FAR;
+// Heads longer than LOOK are re-read only in matrices of at most this many
+// nonzeros; larger ones take the auxiliary array and its second kernel instead.
+// The far part costs the tile kernel 5-8 % on matrices with 64- and 128-entry
+// rows, the second kernel about 3 us and a launch: measured at 8 to 60 M
+// nonzeros, re-reading wins up to 24 M (5-9 % of the SpMV), is level at 32 M and
+// loses beyond (3-5 %).
+constexpr int64_t LOOK_FAR_MAX_NNZ = 28 * 1000 * 1000;
 constexpr int LOOK_MIN_SIGMA = 8, LOOK_MAX_SIGMA = 32;
 constexpr bool look_sigma(int sigma) { return sigma >= LOOK_MIN_SIGMA && sigma <= LOOK_MAX_SIGMA; }
 // Tiles (= wavefronts) per workgroup of the tile kernel and of the transposition,
@@ -198,7 +209,7 @@ __device__ __forceinline__ uint32_t xcd_order(uint32_t w, uint32_t nb, uint32_t 
 // ----------------------------------------------------------------------------
 template <typename IT>
 __global__ void __launch_bounds__(256)
-k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p, int pc, int group,
+k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p, int pc, int group, int record_reach,
            typename Index<IT>::tp_t* __restrict__ tile_ptr, uint32_t* __restrict__ tile_head,
            uint32_t* __restrict__ wg_far, uint32_t* __restrict__ desc, size_t ndesc,
            uint32_t* __restrict__ status) {
@@ -207,7 +218,7 @@ k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p, int pc, int grou
     size_t stride = size_t(gridDim.x) * blockDim.x;
     for (size_t k = gid; k < ndesc; k += stride) desc[k] = 0u;
     if (gid == 0) *status = 0u;
-    int far = 0;
+    int far = 0, far_heads = 0;
     for (size_t t = gid; t <= size_t(p); t += stride) {
         int64_t bnd = int64_t(t) * T;
         const int row = count_le(row_ptr, m + 1, bnd) - 1;
@@ -220,18 +231,21 @@ k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p, int pc, int grou
         tile_head[t] = uint32_t(head < 0 ? 0 : (head > int64_t(0xffffffffu) ? int64_t(0xffffffffu) : head));
         // Can the tile kernel complete that row on its own?  The first tile of a
         // workgroup (and the workgroup of the incomplete tile) re-reads the head
-        // from the previous tile's record: at most LOOK_MAX entries.  The other
+        // from the previous tile's record: at most record_reach entries (LOOK_MAX,
+        // or LOOK in a large matrix, see LOOK_FAR_MAX_NNZ).  The other
         // tiles are handed their neighbour's last segment, which is the whole
         // head if the row began inside (or with) that neighbour: at most T entries.
         const bool from_record = (t % size_t(group)) == 0 || t >= size_t(pc);
-        far |= int(head > (from_record ? int64_t(LOOK_MAX) : int64_t(T)));
+        far |= int(head > (from_record ? int64_t(record_reach) : int64_t(T)));
+        far_heads |= int(from_record && head > int64_t(LOOK));
     }
     // "Some tile starts too far into a row" (the SpMV then needs its
     // carry array) does not go to the status word from here -- this launch also
     // clears that word, and thousands of workgroups saying so would queue at it --
     // but into one word per workgroup, which the scan kernel collects.
     far = __syncthreads_or(far);
-    if (threadIdx.x == 0) wg_far[blockIdx.x] = uint32_t(far != 0);
+    far_heads = __syncthreads_or(far_heads);
+    if (threadIdx.x == 0) wg_far[blockIdx.x] = uint32_t(far != 0) | (uint32_t(far_heads != 0) << 1);   // bit 0, bit 1
 }
 
 // ----------------------------------------------------------------------------
@@ -450,13 +464,22 @@ __device__ __forceinline__ void scan_epilogue(int pc, int p, IT total, IT* __res
         atomicOr(status, CSR5_STATUS_HAS_DIRTY | CSR5_STATUS_HAS_EMPTY_ROWS);
 }
 
-// Did some workgroup of k_tile_ptr (nwg of them) meet a tile that starts more
-// than LOOK entries into a row?  Every thread of the workgroup must call this;
-// all get the answer.
-__device__ __forceinline__ bool any_tile_far(const uint32_t* __restrict__ wg_far, int nwg) {
-    int far = 0;
-    for (int w = threadIdx.x; w < nwg; w += blockDim.x) far |= int(wg_far[w]);
-    return __syncthreads_or(far) != 0;
+// What the workgroups of k_tile_ptr (nwg of them) found about the tiles' heads
+// (bit 0: some tile starts too far into a row for the tile kernel alone; bit 1:
+// some workgroup's first tile starts more than LOOK entries into a row) goes to
+// the status word, once.  Every thread of the workgroup must call this.
+__device__ __forceinline__ uint32_t any_tile_far(const uint32_t* __restrict__ wg_far, int nwg, uint32_t* status) {
+    int far = 0, far_heads = 0;
+    for (int w = threadIdx.x; w < nwg; w += blockDim.x) {
+        const uint32_t bits = wg_far[w];
+        far |= int(bits & 1u);
+        far_heads |= int(bits & 2u);
+    }
+    far = __syncthreads_or(far);
+    far_heads = __syncthreads_or(far_heads);
+    const uint32_t raise = (far ? STATUS_NEEDS_CARRY : 0u) | (far_heads ? STATUS_FAR_HEADS : 0u);
+    if (raise && threadIdx.x == 0) atomicOr(status, raise);
+    return raise;
 }
 
 template <typename IT>
@@ -464,8 +487,7 @@ __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_eop(int pc, int p, IT* __restrict__ eop, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
            const uint32_t* __restrict__ tile_head, const uint32_t* __restrict__ wg_far, int nwg,
            uint32_t* __restrict__ status) {
-    const bool far = any_tile_far(wg_far, nwg);
-    if (far && threadIdx.x == 0) atomicOr(status, STATUS_NEEDS_CARRY);
+    any_tile_far(wg_far, nwg, status);
     IT total = 0;
     if (*status & STATUS_SCAN_NEEDED)
         for (int64_t base = 0; base < pc; base += SCAN_CHUNK) total += scan_chunk(eop, base, int64_t(pc), total);
@@ -490,8 +512,7 @@ k_scan_finish(int pc, int p, IT* __restrict__ eop, const IT* __restrict__ chunk_
               const uint32_t* __restrict__ wg_far, int nwg, uint32_t* __restrict__ status) {
     const int b = blockIdx.x, last = int(gridDim.x) - 1;
     if (b == last) {                                       // uniform over the workgroup
-        const bool far = any_tile_far(wg_far, nwg);
-        if (far && threadIdx.x == 0) atomicOr(status, STATUS_NEEDS_CARRY);
+        any_tile_far(wg_far, nwg, status);
     }
     if (!(*status & STATUS_SCAN_NEEDED)) {
         if (b == last && threadIdx.x == 0) scan_epilogue(pc, p, IT(0), eop, tile_ptr, status);
@@ -613,8 +634,10 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
     // matrix with a tile far into a row never uses (the scan kernel has said so by now).
     // Only a group's last tile is looked at from outside its workgroup; the last
     // complete tile also by the workgroup of the incomplete one.
-    const bool keep_last = !BACK && last_val && last_col && !(*status & STATUS_NEEDS_CARRY) &&
+    const uint32_t st_heads = *status;
+    const bool keep_last = !BACK && last_val && last_col && !(st_heads & STATUS_NEEDS_CARRY) &&
                            (wave == WAVES - 1 || tile == pc - 1);
+    const bool keep_far = keep_last && (st_heads & STATUS_FAR_HEADS);    // nobody reads the far part otherwise
     const size_t rec = size_t(tile) / WAVES;
 
     // ---- val: HBM -> registers -> LDS -> registers -> HBM
@@ -628,13 +651,12 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
             if (keep_last) {
                 VT* const near_v = last_val + rec * last_val_stride<VT>();
                 VT* const far_v = near_v + far_val_at<VT>();
-                if (lane >= OMEGA - LOOK) {
-                    near_v[lane - (OMEGA - LOOK)] = v[SIGMA - 1];
-                    far_v[lane - (OMEGA - LOOK)] = v[SIGMA - 3];
-                } else {
-                    far_v[LOOK_FAR - LOOK + lane] = v[SIGMA - 1];
+                if (lane >= OMEGA - LOOK) near_v[lane - (OMEGA - LOOK)] = v[SIGMA - 1];
+                if (keep_far) {
+                    if (lane >= OMEGA - LOOK) far_v[lane - (OMEGA - LOOK)] = v[SIGMA - 3];
+                    else far_v[LOOK_FAR - LOOK + lane] = v[SIGMA - 1];
+                    far_v[LOOK + lane] = v[SIGMA - 2];
                 }
-                far_v[LOOK + lane] = v[SIGMA - 2];
             }
         }
         if (!BACK) {
@@ -676,13 +698,12 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
             if (keep_last) {
                 int32_t* const near_c = last_col + rec * LAST_COL_STRIDE;
                 int32_t* const far_c = near_c + FAR_COL_AT;
-                if (lane >= OMEGA - LOOK) {
-                    near_c[lane - (OMEGA - LOOK)] = c[SIGMA - 1];
-                    far_c[lane - (OMEGA - LOOK)] = c[SIGMA - 3];
-                } else {
-                    far_c[LOOK_FAR - LOOK + lane] = c[SIGMA - 1];
+                if (lane >= OMEGA - LOOK) near_c[lane - (OMEGA - LOOK)] = c[SIGMA - 1];
+                if (keep_far) {
+                    if (lane >= OMEGA - LOOK) far_c[lane - (OMEGA - LOOK)] = c[SIGMA - 3];
+                    else far_c[LOOK_FAR - LOOK + lane] = c[SIGMA - 1];
+                    far_c[LOOK + lane] = c[SIGMA - 2];
                 }
-                far_c[LOOK + lane] = c[SIGMA - 2];
             }
         }
         if (!BACK) {
@@ -888,7 +909,7 @@ __device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
 
 template <int SIGMA, typename VT, typename IT, bool CAN_LOOK>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
-k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd_chunk,
+k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd_chunk, uint32_t far_mode,
        const IT* __restrict__ row_ptr, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
        const uint32_t* __restrict__ tile_desc, const IT* __restrict__ eop,
        const int32_t* __restrict__ eo, const int32_t* __restrict__ col_idx,
@@ -956,7 +977,11 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     // longer than LOOK also takes the far part of the record, two entries per lane.
     VT head_v = VT(0), head_x = VT(0), far_v0 = VT(0), far_v1 = VT(0), far_prod = VT(0);
     int32_t head_c = 0, far_c0 = 0, far_c1 = 0;
-    const bool far_head = CAN_LOOK && look && wave == 0 && head_len > uint32_t(LOOK);      // uniform
+    // far_mode, from the host: 0 = this matrix has no such head (nobody waits for
+    // head_len then), 1 = it has, or the host does not know yet.  (Taking the far
+    // part without asking whenever the matrix has such heads was slower than
+    // asking: 114 against 110 us on a 53 M-nonzero matrix of 128-entry rows.)
+    const bool far_head = CAN_LOOK && look && wave == 0 && far_mode != 0u && head_len > uint32_t(LOOK);      // uniform
     if constexpr (CAN_LOOK) {
         if (wave == 0) {
             const size_t rec = size_t(tile > 0 ? tile - 1 : 0) / WAVES;      // the group before this one
@@ -964,12 +989,6 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
             const VT* const near_v = last_val + rec * last_val_stride<VT>();
             head_c = near_c[lane & (LOOK - 1)];
             head_v = near_v[lane & (LOOK - 1)];
-            if (far_head) {
-                far_c0 = near_c[FAR_COL_AT + lane];
-                far_c1 = near_c[FAR_COL_AT + OMEGA + lane];
-                far_v0 = near_v[far_val_at<VT>() + lane];
-                far_v1 = near_v[far_val_at<VT>() + OMEGA + lane];
-            }
         }
     }
 
@@ -1028,6 +1047,20 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         IT e0 = eop[tile], e1 = eop[tile + 1];
         eo_t = eo + e0;
         nseg_t = uint32_t(e1 - e0);
+    }
+    // look-behind, the far part of the record.  Asked for only here, behind the
+    // tile's own loads: the decision needs head_len, and a wait for it further up
+    // would hold back the stream of every tile, also of those that never take it.
+    if constexpr (CAN_LOOK) {
+        if (far_head) {
+            const size_t rec = size_t(tile - 1) / WAVES;                  // tile > 0: it has a head
+            const int32_t* const far_c = last_col + rec * LAST_COL_STRIDE + FAR_COL_AT;
+            const VT* const far_v = last_val + rec * last_val_stride<VT>() + far_val_at<VT>();
+            far_c0 = far_c[lane];
+            far_c1 = far_c[OMEGA + lane];
+            far_v0 = far_v[lane];
+            far_v1 = far_v[OMEGA + lane];
+        }
     }
     if ((st & BAD_BITS) || row0_wide >= tp_t(m)) {        // rejected input: gather and store nothing
         if constexpr (CAN_LOOK) __syncthreads();
@@ -1107,8 +1140,8 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         for (int j = 0; j < SIGMA; j++) xv[j] = xb[lane * PITCH + j];
         wave_sync_lds();
         if constexpr (CAN_LOOK) {
-            if (far_head) {     // far entries first .. LOOK_FAR - 1 belong to the head; lane holds entries lane and lane + 64
-                const int first = LOOK_FAR - int(head_len - uint32_t(LOOK));
+            if (far_head) {     // far entries first .. LOOK_FAR - 1 belong to the head (none when it is short); lane holds entries lane and lane + 64
+                const int first = LOOK_FAR + LOOK - int(head_len);
                 if (lane >= first) far_prod = far_v0 * far_x0;
                 if (lane + OMEGA >= first) far_prod = fma(far_v1, far_x1, far_prod);
             }
@@ -1297,7 +1330,7 @@ hipError_t launch_spmv(const Geom& g, int m, int n, IT nnz, const IT* row_ptr,
                        const uint32_t* tile_desc, const IT* eop, const int32_t* eo,
                        const int32_t* col_idx, const VT* val, const VT* x, VT* y,
                        VT* carry, const uint32_t* status, const uint32_t* tile_head, const int32_t* last_col,
-                       const VT* last_val, bool zero_rows, hipStream_t s) {
+                       const VT* last_val, bool zero_rows, uint32_t far_mode, hipStream_t s) {
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
     uint32_t nb_tiles = uint32_t((g.pc + WAVES - 1) / WAVES);
     uint32_t has_tail = (int64_t(g.pc) * g.T < nnz) ? 1u : 0u;
@@ -1313,7 +1346,7 @@ hipError_t launch_spmv(const Geom& g, int m, int n, IT nnz, const IT* row_ptr,
     else if (x_bytes < XCD_CONTIGUOUS_MIN_X_BYTES)                 // x at home in every L2
         xcd_chunk = XCD_CHUNK;
     hipLaunchKernelGGL((k_spmv<SIGMA, VT, IT, CAN_LOOK>), dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, g.p, nb_tiles, has_tail,
-                       xcd_chunk, row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status, tile_head, last_col, last_val);
+                       xcd_chunk, far_mode, row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status, tile_head, last_col, last_val);
     return hipGetLastError();
 }
 
@@ -1607,7 +1640,7 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         if (nb > MAX_TILE_PTR_WG) nb = MAX_TILE_PTR_WG;
         n_far_wg = int(nb);
         hipLaunchKernelGGL(k_tile_ptr<IT>, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p, g.pc,
-                           tile_group_waves(g.sigma), tile_ptr, h->tile_head, wg_far, h->tile_desc, L.ndesc, h->status);
+                           tile_group_waves(g.sigma), int64_t(nnz) <= LOOK_FAR_MAX_NNZ ? LOOK_MAX : LOOK, tile_ptr, h->tile_head, wg_far, h->tile_desc, L.ndesc, h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && m > 0) {   // steps 2b + 3a
@@ -1732,14 +1765,16 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, in
     const bool carries = known < 0 || (uint32_t(known) & STATUS_NEEDS_CARRY) || !h->last_col;
     // the instantiation without the look-behind when the matrix is known not to use it
     const bool can_look = h->last_col && (known < 0 || !(uint32_t(known) & STATUS_NEEDS_CARRY));
+    // can the look-behind of this matrix need the far part of the records
+    const uint32_t far_mode = (known < 0 || (uint32_t(known) & STATUS_FAR_HEADS)) ? 1u : 0u;
     if (which & LAUNCH_TILES) {
 #define X(S) case S: e = (look_sigma(S) && can_look)                                                                \
         ? launch_spmv<S, VT, IT, look_sigma(S)>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, \
               eop, h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y, carry, h->status, h->tile_head,          \
-              h->last_col, static_cast<const VT*>(h->last_val), zero_rows, s)                                        \
+              h->last_col, static_cast<const VT*>(h->last_val), zero_rows, far_mode, s)                              \
         : launch_spmv<S, VT, IT, false>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc,              \
               eop, h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y, carry, h->status, h->tile_head,          \
-              h->last_col, static_cast<const VT*>(h->last_val), zero_rows, s);                                       \
+              h->last_col, static_cast<const VT*>(h->last_val), zero_rows, far_mode, s);                             \
         break;
         switch (h->g.sigma) {
             CSR5_FOR_SIGMA(X)
