@@ -433,6 +433,25 @@ def test_row_lengths_around_the_look_behind_limits(row_len, one_kernel):
         B.csr5_free(h)
 
 
+@pytest.mark.parametrize("sigma", [8, 16, 24])
+def test_single_precision_long_heads(sigma):
+    """Rows of 100 entries in single precision: the look-behind reads the far part
+    of the records (4-byte values in 8-byte slots), the SpMV is one kernel."""
+    a = wl.from_row_lengths(np.full(9000, 100), 3000, seed=77, name="rows100")
+    _run32(a, sigma)
+    dev = torch.device("cuda:0")
+    row_ptr = torch.from_numpy(a.row_ptr).to(dev)
+    col = torch.from_numpy(a.col_idx).to(dev)
+    val = torch.from_numpy(a.val.astype(np.float32)).to(dev)
+    x = torch.from_numpy(a.x.astype(np.float32)).to(dev)
+    y = torch.empty(a.m, dtype=torch.float32, device=dev)
+    h = B.csr5s_convert_ex(a.m, a.n, a.nnz, row_ptr, col, val, sigma=sigma)
+    _, ms_second = B.csr5s_spmv_profile(h, x, y, reps=50)
+    torch.cuda.synchronize()
+    assert ms_second < 1e-3, ms_second
+    B.csr5_free(h)
+
+
 @pytest.mark.parametrize("f32", [False, True])
 def test_bound_call_is_the_same_call(f32):
     """binding.csr5_spmv_bound marshals once and then only makes the C call: the
