@@ -85,8 +85,8 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * word per tile saying how far into its first row the tile starts (p+1) + for
  * 8 <= sigma <= 32 a copy of the last 160 (col_idx, val) pairs in CSR order of every
  * 4th complete tile (every 2nd for sigma > 16) and of the last one (1920 bytes each;
- * it lets a tile finish a row that began in the previous tile without a second
- * kernel) + the conversion's scratch
+ * the last 32 pairs, 384 bytes, when nnz exceeds 28 million; it lets a tile finish
+ * a row that began in the previous tile without a second kernel) + the conversion's scratch
  * (p_c/8192 + 1 + 8192 words) + a status word, each rounded up to 256 bytes.
  * Returns 0 for invalid arguments.
  */

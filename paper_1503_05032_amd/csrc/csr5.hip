@@ -71,9 +71,10 @@ constexpr int tile_group_waves(int sigma) { return sigma <= 16 ? 4 : (sigma <= 3
 // the tile, entry i of the near part entry T - LOOK + i).  Record of tile t:
 // number t / tile_group_waves.  Strides of the two views of the record array
 // (last_val points at a record's first byte, last_col at its near indices):
+// A matrix too large for far heads (LOOK_FAR_MAX_NNZ) keeps the near part only.
+constexpr int NEAR_REC_BYTES = LOOK * 8 + LOOK * 4;
 constexpr int LAST_REC_BYTES = LOOK_MAX * 8 + LOOK_MAX * 4;
-constexpr int LAST_COL_STRIDE = LAST_REC_BYTES / 4;           // in int32
-template <typename VT> constexpr int last_val_stride() { return LAST_REC_BYTES / int(sizeof(VT)); }
+constexpr int record_bytes(int64_t nnz) { return nnz <= LOOK_FAR_MAX_NNZ ? LAST_REC_BYTES : NEAR_REC_BYTES; }
 // where a record's far part begins, counted from last_val / last_col of the record
 template <typename VT> constexpr int far_val_at() { return (LOOK * 8 + LOOK * 4) / int(sizeof(VT)); }
 constexpr int FAR_COL_AT = (LOOK * 8 + LOOK * 4 + LOOK_FAR * 8 - LOOK * 8) / 4;
@@ -618,7 +619,7 @@ __device__ __forceinline__ void wave_sync_lds() {
 template <int SIGMA, bool BACK, typename VT>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
 k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __restrict__ val,
-            uint32_t* __restrict__ status, int32_t* __restrict__ last_col, VT* __restrict__ last_val) {
+            uint32_t* __restrict__ status, int32_t* __restrict__ last_col, VT* __restrict__ last_val, int rec_bytes) {
     constexpr int T = OMEGA * SIGMA;
     constexpr int PITCH = TransposeShape<SIGMA>::PITCH;
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
@@ -637,7 +638,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
     const uint32_t st_heads = *status;
     const bool keep_last = !BACK && last_val && last_col && !(st_heads & STATUS_NEEDS_CARRY) &&
                            (wave == WAVES - 1 || tile == pc - 1);
-    const bool keep_far = keep_last && (st_heads & STATUS_FAR_HEADS);    // nobody reads the far part otherwise
+    const bool keep_far = keep_last && (st_heads & STATUS_FAR_HEADS) && rec_bytes == LAST_REC_BYTES;   // nobody reads the far part otherwise
     const size_t rec = size_t(tile) / WAVES;
 
     // ---- val: HBM -> registers -> LDS -> registers -> HBM
@@ -649,7 +650,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
         // the tile is v[k] here), for the SpMV's look-behind: near part, far part
         if constexpr (!BACK && look_sigma(SIGMA)) {
             if (keep_last) {
-                VT* const near_v = last_val + rec * last_val_stride<VT>();
+                VT* const near_v = last_val + rec * size_t(rec_bytes / int(sizeof(VT)));
                 VT* const far_v = near_v + far_val_at<VT>();
                 if (lane >= OMEGA - LOOK) near_v[lane - (OMEGA - LOOK)] = v[SIGMA - 1];
                 if (keep_far) {
@@ -696,7 +697,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
         }
         if constexpr (!BACK && look_sigma(SIGMA)) {
             if (keep_last) {
-                int32_t* const near_c = last_col + rec * LAST_COL_STRIDE;
+                int32_t* const near_c = last_col + rec * size_t(rec_bytes / 4);
                 int32_t* const far_c = near_c + FAR_COL_AT;
                 if (lane >= OMEGA - LOOK) near_c[lane - (OMEGA - LOOK)] = c[SIGMA - 1];
                 if (keep_far) {
@@ -910,7 +911,7 @@ __device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
 template <int SIGMA, typename VT, typename IT, bool CAN_LOOK>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
 k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd_chunk, uint32_t far_mode,
-       const IT* __restrict__ row_ptr, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
+       int rec_bytes, const IT* __restrict__ row_ptr, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
        const uint32_t* __restrict__ tile_desc, const IT* __restrict__ eop,
        const int32_t* __restrict__ eo, const int32_t* __restrict__ col_idx,
        const VT* __restrict__ val, const VT* __restrict__ x, VT* __restrict__ y,
@@ -941,8 +942,8 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         const tp_t first_row = tile_ptr[pc] & Index<IT>::ROWMASK;
         spmv_tail<VT, IT>(m, nnz, IT(pc) * T, first_row > tp_t(m) ? uint32_t(m) : uint32_t(first_row),
                           row_ptr, col_idx, val, x, y, carry + pc,
-                          (look && pc > 0) ? last_col + size_t((pc - 1) / WAVES) * LAST_COL_STRIDE : nullptr,
-                          (look && pc > 0) ? last_val + size_t((pc - 1) / WAVES) * last_val_stride<VT>() : nullptr);
+                          (look && pc > 0) ? last_col + size_t((pc - 1) / WAVES) * size_t(rec_bytes / 4) : nullptr,
+                          (look && pc > 0) ? last_val + size_t((pc - 1) / WAVES) * size_t(rec_bytes / int(sizeof(VT))) : nullptr);
         return;
     }
     if (blockIdx.x >= has_tail + nb_tiles) {   // workgroups after the tiles: the zeros of rows without nonzeros
@@ -981,12 +982,13 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     // head_len then), 1 = it has, or the host does not know yet.  (Taking the far
     // part without asking whenever the matrix has such heads was slower than
     // asking: 114 against 110 us on a 53 M-nonzero matrix of 128-entry rows.)
-    const bool far_head = CAN_LOOK && look && wave == 0 && far_mode != 0u && head_len > uint32_t(LOOK);      // uniform
+    const bool far_head = CAN_LOOK && look && wave == 0 && far_mode != 0u && head_len > uint32_t(LOOK) &&
+                          rec_bytes == LAST_REC_BYTES;      // uniform (the last test cannot fail: such a matrix has no long head in look mode)
     if constexpr (CAN_LOOK) {
         if (wave == 0) {
             const size_t rec = size_t(tile > 0 ? tile - 1 : 0) / WAVES;      // the group before this one
-            const int32_t* const near_c = last_col + rec * LAST_COL_STRIDE;
-            const VT* const near_v = last_val + rec * last_val_stride<VT>();
+            const int32_t* const near_c = last_col + rec * size_t(rec_bytes / 4);
+            const VT* const near_v = last_val + rec * size_t(rec_bytes / int(sizeof(VT)));
             head_c = near_c[lane & (LOOK - 1)];
             head_v = near_v[lane & (LOOK - 1)];
         }
@@ -1054,8 +1056,8 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     if constexpr (CAN_LOOK) {
         if (far_head) {
             const size_t rec = size_t(tile - 1) / WAVES;                  // tile > 0: it has a head
-            const int32_t* const far_c = last_col + rec * LAST_COL_STRIDE + FAR_COL_AT;
-            const VT* const far_v = last_val + rec * last_val_stride<VT>() + far_val_at<VT>();
+            const int32_t* const far_c = last_col + rec * size_t(rec_bytes / 4) + FAR_COL_AT;
+            const VT* const far_v = last_val + rec * size_t(rec_bytes / int(sizeof(VT))) + far_val_at<VT>();
             far_c0 = far_c[lane];
             far_c1 = far_c[OMEGA + lane];
             far_v0 = far_v[lane];
@@ -1346,7 +1348,7 @@ hipError_t launch_spmv(const Geom& g, int m, int n, IT nnz, const IT* row_ptr,
     else if (x_bytes < XCD_CONTIGUOUS_MIN_X_BYTES)                 // x at home in every L2
         xcd_chunk = XCD_CHUNK;
     hipLaunchKernelGGL((k_spmv<SIGMA, VT, IT, CAN_LOOK>), dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, g.p, nb_tiles, has_tail,
-                       xcd_chunk, far_mode, row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status, tile_head, last_col, last_val);
+                       xcd_chunk, far_mode, record_bytes(int64_t(nnz)), row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status, tile_head, last_col, last_val);
     return hipGetLastError();
 }
 
@@ -1358,7 +1360,7 @@ hipError_t launch_transpose(const Geom& g, int n, int64_t nnz, int32_t* col_idx,
     if (nb == 0) nb = BACK ? 0 : 1;   // forward pass still validates the tail's columns
     if (nb == 0) return hipSuccess;
     hipLaunchKernelGGL((k_transpose<SIGMA, BACK, VT>), dim3(nb), dim3(WAVES * OMEGA), 0, s, g.pc, n, nnz,
-                       col_idx, val, status, last_col, last_val);
+                       col_idx, val, status, last_col, last_val, record_bytes(nnz));
     return hipGetLastError();
 }
 
@@ -1482,7 +1484,7 @@ struct Layout {
     size_t ndesc, eo_cap, carry_slot_bytes;
 };
 
-Layout make_layout(int32_t m, const Geom& g, bool wide) {
+Layout make_layout(int32_t m, int64_t nnz, const Geom& g, bool wide) {
     Layout L;
     const size_t isz = wide ? 8 : 4;   // bytes of one tile_ptr / empty_offset_ptr entry
     L.ndesc = size_t(g.pc) * g.W * OMEGA;
@@ -1499,7 +1501,7 @@ Layout make_layout(int32_t m, const Geom& g, bool wide) {
     L.off_carry = o;    o += L.carry_slot_bytes * CARRY_SLOTS;
     L.has_last = look_sigma(g.sigma) && g.pc > 0;
     const size_t groups = (size_t(g.pc) + tile_group_waves(g.sigma) - 1) / tile_group_waves(g.sigma);
-    L.off_last = o;     o += L.has_last ? align256(groups * LAST_REC_BYTES) : 0;
+    L.off_last = o;     o += L.has_last ? align256(groups * size_t(record_bytes(nnz))) : 0;
     L.off_scan = o;     o += align256((size_t(g.pc) / SCAN_CHUNK + 1) * isz);   // chunk totals of the scan
     L.off_wg_far = o;   o += align256(size_t(MAX_TILE_PTR_WG) * 4);              // one word per workgroup of k_tile_ptr
     L.off_status = o;   o += 256;
@@ -1546,7 +1548,7 @@ size_t csr5_workspace_bytes(int32_t m, int32_t nnz, int32_t sigma) {
     if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
     if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX || !geometry_fits(m, nnz, sigma)) return 0;
     Geom g = make_geom(nnz, sigma);
-    return make_layout(m, g, false).total;
+    return make_layout(m, nnz, g, false).total;
 }
 
 size_t csr5l_workspace_bytes(int32_t m, int64_t nnz, int32_t sigma) {
@@ -1554,7 +1556,7 @@ size_t csr5l_workspace_bytes(int32_t m, int64_t nnz, int32_t sigma) {
     if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
     if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX || !geometry_fits(m, nnz, sigma)) return 0;
     Geom g = make_geom(nnz, sigma);
-    return make_layout(m, g, true).total;
+    return make_layout(m, nnz, g, true).total;
 }
 
 }  // extern "C"
@@ -1580,7 +1582,7 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
     Geom g = make_geom(nnz, sigma);
-    Layout L = make_layout(m, g, wide);
+    Layout L = make_layout(m, nnz, g, wide);
     csr5_handle_s* h = new (std::nothrow) csr5_handle_s();
     if (!h) return CSR5_ENOMEM;
     char* basep = nullptr;

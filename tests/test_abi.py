@@ -69,6 +69,13 @@ def test_workspace_bytes(lib):
     need24 = ((p24 + 1) * 4 + pc24 * oracle.desc_words(64, 24) * 64 * 4 + (pc24 + 1) * 4 + min(m + pc24, pc24 * T24) * 4
               + 4 * (p24 + 1) * 8 + 4 + -(-pc24 // 2) * 160 * (4 + 8) + (p24 + 1) * 4 + 8192 * 4)
     assert need24 <= B.csr5_workspace_bytes(m, nnz, 24) <= need24 + 14 * 256
+    # beyond 28 million nonzeros the copies hold 32 entries
+    mb, nb = 3_000_000, 40_000_000
+    Tb = 64 * 16
+    pb, pcb = -(-nb // Tb), nb // Tb
+    needb = ((pb + 1) * 4 + pcb * 64 * 4 + (pcb + 1) * 4 + min(mb + pcb, pcb * Tb) * 4 + 4 * (pb + 1) * 8 + 4
+             + -(-pcb // 4) * 32 * (4 + 8) + (pb + 1) * 4 + 8192 * 4)
+    assert needb <= B.csr5_workspace_bytes(mb, nb, 16) <= needb + 14 * 256
     # no such copy below sigma 8
     p4, pc4 = -(-nnz // 256), nnz // 256
     need4 = (p4 + 1) * 4 + pc4 * 64 * 4 + (pc4 + 1) * 4 + min(m + pc4, pc4 * 256) * 4 + 4 * (p4 + 1) * 8 + 4 + (p4 + 1) * 4 + 8192 * 4

@@ -433,6 +433,24 @@ def test_row_lengths_around_the_look_behind_limits(row_len, one_kernel):
         B.csr5_free(h)
 
 
+def test_stencil_beyond_the_far_record_limit():
+    """A 27-point stencil with more than 28 million nonzeros: its look-behind
+    records hold the near part only (a different record stride), the SpMV is
+    still one kernel, format and result are the oracle's."""
+    a = wl.stencil27(g=104)
+    assert a.nnz > 28_000_000
+    d = DeviceCsr(a)
+    h = convert(d, sigma=16)
+    say("stencil 104^3", a.nnz)
+    check_format(d, h, (a.name, 16))
+    check_spmv(d, h, (a.name, 16))
+    _, ms_second = B.csr5_spmv_profile(h, d.x, d.y, reps=20)
+    torch.cuda.synchronize()
+    assert ms_second < 1e-3, ms_second
+    _check_y(d.y.cpu().numpy()[:a.m], a, "after profile")
+    B.csr5_free(h)
+
+
 @pytest.mark.parametrize("sigma", [8, 16, 24])
 def test_single_precision_long_heads(sigma):
     """Rows of 100 entries in single precision: the look-behind reads the far part
