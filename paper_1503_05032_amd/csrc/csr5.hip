@@ -1289,8 +1289,7 @@ template <typename VT, typename IT>
 __global__ void __launch_bounds__(FLOOR_WAVES * OMEGA)
 k_stream_floor(int m, int pc, int sigma, int W, uint32_t nb_tiles, uint32_t xcd_chunk, int write_y,
                const typename Index<IT>::tp_t* __restrict__ tile_ptr, const uint32_t* __restrict__ tile_desc,
-               const int32_t* __restrict__ col_idx, const VT* __restrict__ val, VT* __restrict__ y,
-               uint32_t* __restrict__ sink) {
+               const int32_t* __restrict__ col_idx, const VT* __restrict__ val, VT* __restrict__ y) {
     typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / OMEGA);
@@ -1322,7 +1321,7 @@ k_stream_floor(int m, int pc, int sigma, int W, uint32_t nb_tiles, uint32_t xcd_
         if (r1 > uint32_t(m)) r1 = uint32_t(m);
         for (uint32_t r = r0 + lane; r < r1; r += OMEGA) y[r] = VT(acc);
     } else if (acc == 0x5a17c0de) {
-        sink[0] = uint32_t(acc);           // keeps the loads alive; practically never taken
+        y[0] = VT(acc);                    // keeps the loads alive; practically never taken (y is scratch here)
     }
 }
 
@@ -1881,8 +1880,7 @@ static int stream_floor(csr5_handle_t h, VT* y, hipStream_t s, int reps, float* 
         for (int r = 0; rc == CSR5_OK && r < reps; r++) {
             hipLaunchKernelGGL((k_stream_floor<VT, IT>), dim3(nb_tiles), dim3(FLOOR_WAVES * OMEGA), 0, s, h->m, g.pc,
                                g.sigma, g.W, nb_tiles, xcd_chunk, pass, static_cast<const tp_t*>(h->tile_ptr),
-                               h->tile_desc, h->col_idx, static_cast<const VT*>(h->val), y,
-                               static_cast<uint32_t*>(h->carry));
+                               h->tile_desc, h->col_idx, static_cast<const VT*>(h->val), y);
             if (hipGetLastError() != hipSuccess) rc = CSR5_EHIP;
         }
     }
