@@ -30,6 +30,44 @@ def test_header_symbols_exported(lib):
         assert hasattr(raw, name), name
 
 
+def test_header_is_plain_c_and_links(lib, tmp_path):
+    """The boundary is a C ABI: a C99 program that includes the header compiles
+    without warnings, links against the library, and its host-only calls work
+    without a GPU."""
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no gcc")
+    src = tmp_path / "use_csr5.c"
+    src.write_text("""
+#include <stdio.h>
+#include <string.h>
+#include "csr5.h"
+int main(void) {
+    csr5_handle_t h = NULL;
+    if (csr5_sigma_auto(27000000, 1000000) <= 0) return 1;
+    if (csr5_workspace_bytes(1000, 26000, 16) == 0) return 2;
+    if (csr5_workspace_bytes(-1, 10, 4) != 0) return 3;
+    if (strcmp(csr5_strerror(CSR5_OK), "ok") != 0) return 4;
+    if (csr5_convert_ex(-1, 1, 0, NULL, NULL, NULL, 0, NULL, 0, NULL, CSR5_FLAG_NONE, &h) != CSR5_EINVAL) return 5;
+    if (h != NULL) return 6;
+    if (csr5_free(NULL) != CSR5_OK) return 7;
+    printf("%d %d\\n", CSR5_OMEGA, CSR5_SIGMA_MAX);
+    return 0;
+}
+""")
+    exe = tmp_path / "use_csr5"
+    libdir = os.path.dirname(B.LIB_PATH)
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+           str(src), "-o", str(exe), "-L", libdir, "-l:" + os.path.basename(B.LIB_PATH), "-Wl,-rpath," + libdir,
+           "-Wl,-rpath,/opt/rocm/lib"]
+    r = subprocess.run(cmd, capture_output=True, text=True, stdin=subprocess.DEVNULL, timeout=120)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, stdin=subprocess.DEVNULL, timeout=60)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    assert r.stdout.split() == ["64", "48"]
+
+
 def test_sigma_rule_matches_paper_shape(lib):
     # The library's rule is the four-way map of Section 3.2 with its own constants.
     # Recover them from its behaviour on a matrix large enough that the
