@@ -21,7 +21,7 @@ constexpr int OMEGA = CSR5_OMEGA;
 constexpr int SBITS = 6;  // ceil(log2 omega)
 constexpr uint32_t BAD_BITS = CSR5_STATUS_BAD_ROW_PTR | CSR5_STATUS_BAD_COL_IDX;
 // Internal status bit (not reported): some COMPLETE tile is marked, so the
-// empty_offset layout has to be scanned.  Set by k_tile_desc only; the scan
+// empty_offset layout has to be scanned.  Set by the descriptor step of k_transpose only; the scan
 // kernels decide on it, and nothing in their own launches changes it.
 constexpr uint32_t STATUS_SCAN_NEEDED = 1u << 16;
 // Internal status bit: some tile (the incomplete one included) starts further
@@ -249,8 +249,27 @@ k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p, int pc, int grou
     if (threadIdx.x == 0) wg_far[blockIdx.x] = uint32_t(far != 0) | (uint32_t(far_heads != 0) << 1);   // bit 0, bit 1
 }
 
+// What the workgroups of k_tile_ptr (nwg of them) found about the tiles' heads
+// (bit 0: some tile starts too far into a row for the tile kernel alone; bit 1:
+// some workgroup's first tile starts more than LOOK entries into a row) goes to
+// the status word, once.  Every thread of the workgroup must call this.
+__device__ __forceinline__ uint32_t any_tile_far(const uint32_t* __restrict__ wg_far, int nwg, uint32_t* status) {
+    int far = 0, far_heads = 0;
+    for (int w = threadIdx.x; w < nwg; w += blockDim.x) {
+        const uint32_t bits = wg_far[w];
+        far |= int(bits & 1u);
+        far_heads |= int(bits & 2u);
+    }
+    far = __syncthreads_or(far);
+    far_heads = __syncthreads_or(far_heads);
+    const uint32_t raise = (far ? STATUS_NEEDS_CARRY : 0u) | (far_heads ? STATUS_FAR_HEADS : 0u);
+    if (raise && threadIdx.x == 0) atomicOr(status, raise);
+    return raise;
+}
+
 // ----------------------------------------------------------------------------
-// Conversion steps 2b + 3a, one thread per matrix row.
+// Conversion steps 2b + 3a, one thread per matrix row (the first workgroup also
+// passes on what k_tile_ptr noted about the tiles' heads).
 //  * empty row   -> mark the tile whose row range holds it (Algorithm 4, second
 //    loop, turned inside out: the printed loop walks each tile's rows, which
 //    serialises on a tile that spans millions of empty rows).  An empty row
@@ -266,9 +285,12 @@ k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p, int pc, int grou
 template <typename IT>
 __global__ void __launch_bounds__(256)
 k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, int p, int pc,
-       typename Index<IT>::tp_t* tile_ptr, uint32_t* desc, uint32_t* status) {
+       typename Index<IT>::tp_t* tile_ptr, uint32_t* desc, const uint32_t* __restrict__ wg_far, int nwg,
+       uint32_t* status) {
     using tp_t = typename Index<IT>::tp_t;
     constexpr tp_t DIRTY = Index<IT>::DIRTY;
+    // what k_tile_ptr found about the tiles' heads, for the transposition that follows
+    if (blockIdx.x == 0) any_tile_far(wg_far, nwg, status);
     const int lane = lane_id();
     const int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     const bool in = g < int64_t(m);                       // every lane stays for the shuffles below
@@ -319,85 +341,11 @@ k_rows(int m, IT nnz, const IT* __restrict__ row_ptr, int sigma, int T, int W, i
     if (sets && (lane == OMEGA - 1 || wnext != word)) atomicOr(&desc[word], bits);
 }
 
-// ----------------------------------------------------------------------------
-// Conversion step 3b, one wavefront per complete tile, lane = tile column:
-// forced first flag, y_offset = exclusive scan of the columns' flag counts,
-// seg_offset = run of flag-less columns to the right (Algorithm 5; the scan and
-// the run length are wavefront operations here), packing (Section 3.5), and the
-// tile's segment count for the empty_offset layout.
-// ----------------------------------------------------------------------------
-template <typename IT>
-__global__ void __launch_bounds__(256)
-k_tile_desc(int sigma, int W, int ybits, int pc, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
-            uint32_t* __restrict__ desc, IT* __restrict__ eop, uint32_t* __restrict__ status) {
-    const int lane = lane_id();
-    const int nwaves = int(gridDim.x) * (blockDim.x / OMEGA);
-    const int first = blockIdx.x * (blockDim.x / OMEGA) + (threadIdx.x / OMEGA);
-    // A tile is 256 bytes of work and one memory round trip: the grid is capped,
-    // every wavefront takes several tiles, and it requests UNROLL of them at once.
-    constexpr int UNROLL = 4;
-    bool met_marked = false;
-    for (int t0 = first; t0 < pc; t0 += UNROLL * nwaves) {
-        uint64_t flags_u[UNROLL];
-        bool dirty_u[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; u++) {
-            const int tile = t0 + u * nwaves;
-            flags_u[u] = 0;
-            dirty_u[u] = false;
-            if (tile < pc) {
-                const size_t base = size_t(tile) * W * OMEGA + lane;
-                flags_u[u] = desc[base];
-                if (sigma > 32) flags_u[u] |= uint64_t(desc[base + OMEGA]) << 32;
-                dirty_u[u] = (tile_ptr[tile] & Index<IT>::DIRTY) != 0;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UNROLL; u++) {
-            const int tile = t0 + u * nwaves;
-            if (tile >= pc) break;                          // uniform over the wavefront
-            const size_t base = size_t(tile) * W * OMEGA + lane;
-            uint64_t flags = flags_u[u];
-            if (lane == 0) flags |= 1u;
-            int cnt = __popcll(flags);
-            int incl = cnt;
-#pragma unroll
-            for (int d = 1; d < OMEGA; d <<= 1) {
-                int up = __shfl_up(incl, d, OMEGA);
-                if (lane >= d) incl += up;
-            }
-            uint32_t yo = uint32_t(incl - cnt);
-            int total = __shfl(incl, OMEGA - 1, OMEGA);
-            uint64_t heads = __ballot(cnt > 0);
-            uint64_t right = (lane == OMEGA - 1) ? 0ull : (heads >> (lane + 1));
-            uint32_t so = 0;
-            if (cnt > 0) so = right ? uint32_t(__builtin_ctzll(right)) : uint32_t(OMEGA - 1 - lane);
-            // little-endian bit field: flags | seg_offset << sigma | y_offset << (sigma+6)
-            int ysh = sigma + SBITS;  // <= 54
-            uint64_t lo = flags | (uint64_t(so) << sigma) | (uint64_t(yo) << ysh);
-            uint64_t hi = (ysh + ybits > 64) ? (uint64_t(yo) >> (64 - ysh)) : 0ull;
-            desc[base] = uint32_t(lo);
-            if (W > 1) desc[base + OMEGA] = uint32_t(lo >> 32);
-            if (W > 2) desc[base + 2 * OMEGA] = uint32_t(hi);
-            if (lane == 0) eop[tile] = dirty_u[u] ? total : 0;
-            met_marked |= dirty_u[u];
-        }
-    }
-    // "some tile is marked" (and hence "some row is empty"): once per workgroup, not
-    // once per empty row -- everything that aims at the one status word queues up
-    __shared__ int wg_met_marked;
-    if (threadIdx.x == 0) wg_met_marked = 0;
-    __syncthreads();
-    if (met_marked && lane == 0) wg_met_marked = 1;
-    __syncthreads();
-    if (threadIdx.x == 0 && wg_met_marked)
-        raise_status(status, CSR5_STATUS_HAS_DIRTY | CSR5_STATUS_HAS_EMPTY_ROWS | STATUS_SCAN_NEEDED);
-}
 
 // ----------------------------------------------------------------------------
 // empty_offset layout: exclusive prefix sum of the per-tile segment counts
 // (non-zero only for tiles with an empty row); the array has p_c + 1 entries.
-// Nothing to scan when no tile is marked (status bit from k_tile_desc).  Up to
+// Nothing to scan when no tile is marked (status bit from the descriptor step of k_transpose).  Up to
 // SCAN_SINGLE tiles one workgroup walks the array chunk by chunk; beyond that
 // every chunk gets a workgroup (local scan + chunk total) and a second launch
 // adds to every chunk the sum of the totals before it.
@@ -454,7 +402,7 @@ __device__ IT scan_chunk(IT* __restrict__ a, int64_t base, int64_t len, IT carry
 }
 
 // The last words of the scan: the total number of entries, and the status bits
-// for a marked incomplete tile (it has no descriptor, so k_tile_desc never sees
+// for a marked incomplete tile (it has no descriptor, so the descriptor step never sees
 // it).  One thread.
 template <typename IT>
 __device__ __forceinline__ void scan_epilogue(int pc, int p, IT total, IT* __restrict__ eop,
@@ -465,30 +413,10 @@ __device__ __forceinline__ void scan_epilogue(int pc, int p, IT total, IT* __res
         atomicOr(status, CSR5_STATUS_HAS_DIRTY | CSR5_STATUS_HAS_EMPTY_ROWS);
 }
 
-// What the workgroups of k_tile_ptr (nwg of them) found about the tiles' heads
-// (bit 0: some tile starts too far into a row for the tile kernel alone; bit 1:
-// some workgroup's first tile starts more than LOOK entries into a row) goes to
-// the status word, once.  Every thread of the workgroup must call this.
-__device__ __forceinline__ uint32_t any_tile_far(const uint32_t* __restrict__ wg_far, int nwg, uint32_t* status) {
-    int far = 0, far_heads = 0;
-    for (int w = threadIdx.x; w < nwg; w += blockDim.x) {
-        const uint32_t bits = wg_far[w];
-        far |= int(bits & 1u);
-        far_heads |= int(bits & 2u);
-    }
-    far = __syncthreads_or(far);
-    far_heads = __syncthreads_or(far_heads);
-    const uint32_t raise = (far ? STATUS_NEEDS_CARRY : 0u) | (far_heads ? STATUS_FAR_HEADS : 0u);
-    if (raise && threadIdx.x == 0) atomicOr(status, raise);
-    return raise;
-}
-
 template <typename IT>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_eop(int pc, int p, IT* __restrict__ eop, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
-           const uint32_t* __restrict__ tile_head, const uint32_t* __restrict__ wg_far, int nwg,
            uint32_t* __restrict__ status) {
-    any_tile_far(wg_far, nwg, status);
     IT total = 0;
     if (*status & STATUS_SCAN_NEEDED)
         for (int64_t base = 0; base < pc; base += SCAN_CHUNK) total += scan_chunk(eop, base, int64_t(pc), total);
@@ -509,12 +437,8 @@ k_scan_chunks(int pc, IT* __restrict__ eop, IT* __restrict__ chunk_sum, const ui
 template <typename IT>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_finish(int pc, int p, IT* __restrict__ eop, const IT* __restrict__ chunk_sum,
-              const typename Index<IT>::tp_t* __restrict__ tile_ptr, const uint32_t* __restrict__ tile_head,
-              const uint32_t* __restrict__ wg_far, int nwg, uint32_t* __restrict__ status) {
+              const typename Index<IT>::tp_t* __restrict__ tile_ptr, uint32_t* __restrict__ status) {
     const int b = blockIdx.x, last = int(gridDim.x) - 1;
-    if (b == last) {                                       // uniform over the workgroup
-        any_tile_far(wg_far, nwg, status);
-    }
     if (!(*status & STATUS_SCAN_NEEDED)) {
         if (b == last && threadIdx.x == 0) scan_epilogue(pc, p, IT(0), eop, tile_ptr, status);
         return;
@@ -619,8 +543,11 @@ __device__ __forceinline__ void wave_sync_lds() {
 template <int SIGMA, bool BACK, typename VT>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
 k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __restrict__ val,
-            uint32_t* __restrict__ status, int32_t* __restrict__ last_col, VT* __restrict__ last_val, int rec_bytes) {
+            uint32_t* __restrict__ status, int32_t* __restrict__ last_col, VT* __restrict__ last_val, int rec_bytes,
+            const void* __restrict__ tile_ptr, uint32_t* __restrict__ desc, void* __restrict__ eop, int wide) {
     constexpr int T = OMEGA * SIGMA;
+    constexpr int YBITS = 32 - __builtin_clz(uint32_t(T - 1));        // ceil(log2(64*sigma))
+    constexpr int W = (SIGMA + SBITS + YBITS + 31) / 32;
     constexpr int PITCH = TransposeShape<SIGMA>::PITCH;
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
     __shared__ double lds[WAVES][OMEGA * PITCH];
@@ -640,6 +567,20 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
                            (wave == WAVES - 1 || tile == pc - 1);
     const bool keep_far = keep_last && (st_heads & STATUS_FAR_HEADS) && rec_bytes == LAST_REC_BYTES;   // nobody reads the far part otherwise
     const size_t rec = size_t(tile) / WAVES;
+
+    // ---- conversion step 3b rides along (forward pass): the tile's flag words,
+    // as k_rows left them, are asked for now and turned into descriptors below
+    uint64_t flags = 0;
+    bool marked = false;
+    const size_t dbase = size_t(active ? tile : 0) * W * OMEGA + lane;
+    if constexpr (!BACK) {
+        if (active && desc) {
+            flags = desc[dbase];
+            if (SIGMA > 32) flags |= uint64_t(desc[dbase + OMEGA]) << 32;
+            marked = wide ? (static_cast<const uint64_t*>(tile_ptr)[tile] >> 63) != 0
+                          : (static_cast<const uint32_t*>(tile_ptr)[tile] >> 31) != 0;
+        }
+    }
 
     // ---- val: HBM -> registers -> LDS -> registers -> HBM
     VT v[SIGMA];
@@ -740,6 +681,52 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
         }
     }
     if (!BACK && bad) raise_status(status, CSR5_STATUS_BAD_COL_IDX);
+
+    // ---- conversion step 3b, lane = tile column: forced first flag, y_offset =
+    // exclusive scan of the columns' flag counts, seg_offset = run of flag-less
+    // columns to the right (Algorithm 5; the scan and the run length are wavefront
+    // operations here), packing (Section 3.5), and the tile's segment count for
+    // the empty_offset layout.
+    if constexpr (!BACK) {
+        if (desc) {                                        // uniform over the grid
+            if (active) {
+                if (lane == 0) flags |= 1u;
+                const int cnt = __popcll(flags);
+                int incl = cnt;
+#pragma unroll
+                for (int d = 1; d < OMEGA; d <<= 1) {
+                    const int up = __shfl_up(incl, d, OMEGA);
+                    if (lane >= d) incl += up;
+                }
+                const uint32_t yo = uint32_t(incl - cnt);
+                const int total = __shfl(incl, OMEGA - 1, OMEGA);
+                const uint64_t heads = __ballot(cnt > 0);
+                const uint64_t right = (lane == OMEGA - 1) ? 0ull : (heads >> (lane + 1));
+                uint32_t so = 0;
+                if (cnt > 0) so = right ? uint32_t(__builtin_ctzll(right)) : uint32_t(OMEGA - 1 - lane);
+                // little-endian bit field: flags | seg_offset << sigma | y_offset << (sigma+6)
+                constexpr int YSH = SIGMA + SBITS;  // <= 54
+                const uint64_t lo = flags | (uint64_t(so) << SIGMA) | (uint64_t(yo) << YSH);
+                const uint64_t hi = (YSH + YBITS > 64) ? (uint64_t(yo) >> (64 - YSH)) : 0ull;
+                desc[dbase] = uint32_t(lo);
+                if (W > 1) desc[dbase + OMEGA] = uint32_t(lo >> 32);
+                if (W > 2) desc[dbase + 2 * OMEGA] = uint32_t(hi);
+                if (lane == 0) {
+                    if (wide) static_cast<int64_t*>(eop)[tile] = marked ? total : 0;
+                    else static_cast<int32_t*>(eop)[tile] = marked ? total : 0;
+                }
+            }
+            // "some tile is marked" (and hence "some row is empty"): once per workgroup, not
+            // once per tile -- everything that aims at the one status word queues up
+            __shared__ int wg_met_marked;
+            if (threadIdx.x == 0) wg_met_marked = 0;
+            __syncthreads();
+            if (active && marked && lane == 0) wg_met_marked = 1;
+            __syncthreads();
+            if (threadIdx.x == 0 && wg_met_marked)
+                raise_status(status, CSR5_STATUS_HAS_DIRTY | CSR5_STATUS_HAS_EMPTY_ROWS | STATUS_SCAN_NEEDED);
+        }
+    }
 }
 
 // ----------------------------------------------------------------------------
@@ -1353,13 +1340,14 @@ hipError_t launch_spmv(const Geom& g, int m, int n, IT nnz, const IT* row_ptr,
 
 template <int SIGMA, bool BACK, typename VT>
 hipError_t launch_transpose(const Geom& g, int n, int64_t nnz, int32_t* col_idx, VT* val,
-                            uint32_t* status, int32_t* last_col, VT* last_val, hipStream_t s) {
+                            uint32_t* status, int32_t* last_col, VT* last_val, const void* tile_ptr,
+                            uint32_t* desc, void* eop, int wide, hipStream_t s) {
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
     uint32_t nb = uint32_t((g.pc + WAVES - 1) / WAVES);
     if (nb == 0) nb = BACK ? 0 : 1;   // forward pass still validates the tail's columns
     if (nb == 0) return hipSuccess;
     hipLaunchKernelGGL((k_transpose<SIGMA, BACK, VT>), dim3(nb), dim3(WAVES * OMEGA), 0, s, g.pc, n, nnz,
-                       col_idx, val, status, last_col, last_val, record_bytes(nnz));
+                       col_idx, val, status, last_col, last_val, record_bytes(nnz), tile_ptr, desc, eop, wide);
     return hipGetLastError();
 }
 
@@ -1646,19 +1634,21 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     }
     if (e == hipSuccess && m > 0) {   // steps 2b + 3a
         hipLaunchKernelGGL(k_rows<IT>, dim3(uint32_t((size_t(m) + 255) / 256)), dim3(256), 0, s, m, nnz,
-                           row_ptr, g.sigma, g.T, g.W, g.p, g.pc, tile_ptr, h->tile_desc, h->status);
+                           row_ptr, g.sigma, g.T, g.W, g.p, g.pc, tile_ptr, h->tile_desc, wg_far, n_far_wg, h->status);
         e = hipGetLastError();
     }
-    if (e == hipSuccess && g.pc > 0) {   // step 3b
-        uint32_t nb = uint32_t((g.pc + 3) / 4);
-        if (nb > 4096) nb = 4096;                          // 64 wavefronts per CU
-        hipLaunchKernelGGL(k_tile_desc<IT>, dim3(nb), dim3(256), 0, s, g.sigma, g.W,
-                           g.ybits, g.pc, tile_ptr, h->tile_desc, eop, h->status);
-        e = hipGetLastError();
+    if (e == hipSuccess && nnz > 0) {   // steps 3b (descriptors, inside the same kernel) + 4
+        switch (sigma) {
+#define X(S) case S: e = launch_transpose<S, false, VT>(g, n, nnz, col_idx, val, h->status, h->last_col,      \
+                                                        static_cast<VT*>(h->last_val), tile_ptr, h->tile_desc, \
+                                                        eop, wide ? 1 : 0, s); break;
+            CSR5_FOR_SIGMA(X)
+#undef X
+            default: e = hipErrorInvalidValue;
+        }
     }
     if (e == hipSuccess && g.pc <= SCAN_SINGLE) {
-        hipLaunchKernelGGL(k_scan_eop<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, tile_ptr, h->tile_head, wg_far,
-                           n_far_wg, h->status);
+        hipLaunchKernelGGL(k_scan_eop<IT>, dim3(1), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, tile_ptr, h->status);
         e = hipGetLastError();
     } else if (e == hipSuccess) {
         IT* chunk_sum = reinterpret_cast<IT*>(basep + L.off_scan);
@@ -1667,7 +1657,7 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         e = hipGetLastError();
         if (e == hipSuccess) {
             hipLaunchKernelGGL(k_scan_finish<IT>, dim3(nchunks), dim3(SCAN_THREADS), 0, s, g.pc, g.p, eop, chunk_sum,
-                               tile_ptr, h->tile_head, wg_far, n_far_wg, h->status);
+                               tile_ptr, h->status);
             e = hipGetLastError();
         }
     }
@@ -1677,15 +1667,6 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
                            row_ptr, g.sigma, g.T, g.W, g.pc, tile_ptr, h->tile_desc, eop, h->eo,
                            h->status);
         e = hipGetLastError();
-    }
-    if (e == hipSuccess && nnz > 0) {   // step 4
-        switch (sigma) {
-#define X(S) case S: e = launch_transpose<S, false, VT>(g, n, nnz, col_idx, val, h->status, h->last_col,      \
-                                                        static_cast<VT*>(h->last_val), s); break;
-            CSR5_FOR_SIGMA(X)
-#undef X
-            default: e = hipErrorInvalidValue;
-        }
     }
     if (e != hipSuccess) {
         (void)hipStreamSynchronize(s);
@@ -1941,9 +1922,9 @@ int csr5_to_csr(csr5_handle_t h, void* hip_stream) {
         switch (h->g.sigma) {
 #define X(S) case S: e = (h->dtype == CSR5_DTYPE_F32)                                                            \
         ? launch_transpose<S, true, float>(h->g, h->n, h->nnz, h->col_idx, static_cast<float*>(h->val), h->status,     \
-                                           nullptr, nullptr, s)                                                         \
+                                           nullptr, nullptr, nullptr, nullptr, nullptr, 0, s)                           \
         : launch_transpose<S, true, double>(h->g, h->n, h->nnz, h->col_idx, static_cast<double*>(h->val), h->status,   \
-                                            nullptr, nullptr, s);                                                       \
+                                            nullptr, nullptr, nullptr, nullptr, nullptr, 0, s);                         \
         break;
             CSR5_FOR_SIGMA(X)
 #undef X
