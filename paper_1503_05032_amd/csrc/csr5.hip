@@ -1627,7 +1627,9 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         size_t work = L.ndesc > size_t(g.p) + 1 ? L.ndesc : size_t(g.p) + 1;
         size_t nb = (work + 255) / 256;
         if (nb > MAX_TILE_PTR_WG) nb = MAX_TILE_PTR_WG;
-        n_far_wg = int(nb);
+        // only the workgroups that hold tile boundaries (thread g of the grid takes tile g first) have anything to say
+        const size_t with_tiles = (size_t(g.p) + 1 + 255) / 256;
+        n_far_wg = int(with_tiles < nb ? with_tiles : nb);
         hipLaunchKernelGGL(k_tile_ptr<IT>, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p, g.pc,
                            tile_group_waves(g.sigma), int64_t(nnz) <= LOOK_FAR_MAX_NNZ ? LOOK_MAX : LOOK, tile_ptr, h->tile_head, wg_far, h->tile_desc, L.ndesc, h->status);
         e = hipGetLastError();
