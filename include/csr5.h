@@ -86,7 +86,11 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * 8 <= sigma <= 32 a copy of the last 160 (col_idx, val) pairs in CSR order of every
  * 4th complete tile (every 2nd for sigma > 16) and of the last one (1920 bytes each;
  * the last 32 pairs, 384 bytes, when nnz exceeds 28 million; it lets a tile finish
- * a row that began in the previous tile without a second kernel) + the conversion's scratch
+ * a row that began in the previous tile without a second kernel) + for 8 <= sigma <= 32
+ * and at most 32768 tiles what the one-kernel form of the auxiliary-array path
+ * needs (per tile: two words naming the groups of tiles its first row touches,
+ * and, with each of the four auxiliary arrays, an 8-byte meeting word and a
+ * counter) + the conversion's scratch
  * (p_c/8192 + 1 + 8192 words) + a status word, each rounded up to 256 bytes.
  * Returns 0 for invalid arguments.
  */
@@ -145,8 +149,14 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, i
  * every matrix without a row longer than 33, and up to 28 million nonzeros every
  * matrix without a row longer than 161), it adds the head itself and stores the
  * finished row, and the SpMV is ONE kernel; otherwise those segments go through
- * an auxiliary array that a second small kernel adds to y (Section 4's "global
- * auxiliary array").  Which of the two, and whether rows without nonzeros need
+ * an auxiliary array (Section 4's "global auxiliary array").  Its sums are added
+ * to y by a second small kernel, or, where that is faster (8 <= sigma <= 32 and
+ * at most 6144 tiles, or at most 32768 tiles and fewer than 64 nonzeros per row
+ * on average), inside the tile kernel: the tiles of a workgroup settle their
+ * common rows through LDS, workgroups meet at a word of the array per row (one
+ * atomic exchange each when the row touches two workgroups' tiles, a counter
+ * otherwise), nobody waits, and whoever comes last stores the row -- again ONE
+ * kernel.  Which of these, and whether rows without nonzeros need
  * their zeros written, is in the conversion's status word: the library launches
  * only what the matrix needs once the host has seen that word (csr5_convert and
  * csr5_convert_ex without CSR5_FLAG_NO_HOST_CHECK read it; after an asynchronous
@@ -154,9 +164,9 @@ int csr5_convert_ex(int32_t m, int32_t n, int32_t nnz, const int32_t *row_ptr, i
  * a few microseconds slower.
  * x double[n], y double[m]; y is overwritten (rows without nonzeros get 0).  x
  * and y must not overlap.  Asynchronous.  Summation order differs from CSR
- * order; rows summed through the auxiliary array by more than one wavefront and
+ * order; rows that the second kernel sums with more than one wavefront and
  * rows cut inside the incomplete tile are added up atomically, so their last
- * bits may differ between runs.  The handle holds four auxiliary arrays, taken
+ * bits may differ between runs (the one-kernel forms add in a fixed order).  The handle holds four auxiliary arrays, taken
  * in turn by successive calls: up to four SpMVs on ONE handle may be in flight at
  * the same time (on different streams); a fifth must be ordered after the first.
  */
@@ -171,9 +181,11 @@ int csr5_spmv_ex(csr5_handle_t h, const double *x, double *y, void *hip_stream);
  * the handle's own.  No hipMalloc, hipFree or other allocating call is made.
  * Same arguments, same result and same error codes as csr5_spmv_ex (double
  * precision, either index width), plus CSR5_ERANGE when the handle has more than
- * CSR5_STATIC_MAX_TILES tiles (p, the incomplete tile included).  Every slot the
- * second kernel reads has been written by the first, so nothing needs clearing
- * between calls.  All calls on one GPU share the array, whatever their handle:
+ * CSR5_STATIC_MAX_TILES tiles (p, the incomplete tile included).  A matrix that
+ * takes the auxiliary-array path always gets the two-kernel form here (the
+ * one-kernel form keeps words of its own between calls, which a shared array
+ * cannot promise).  Every slot the second kernel reads has been written by the
+ * first, so nothing needs clearing between calls.  All calls on one GPU share the array, whatever their handle:
  * calls that overlap in time on one GPU race; order them (one stream, or events).
  */
 #define CSR5_STATIC_SCRATCH_BYTES (4u << 20)
@@ -292,7 +304,8 @@ const char *csr5_strerror(int code);
  * row on the stream, HIP events before and after each series, waits, and returns
  * the mean duration per launch in milliseconds: ms[0] the tile kernel (all
  * complete tiles plus the workgroup for the incomplete one), ms[1] the carry
- * fix-up (0 when this matrix does not need it).  ms is a host array of 2 floats.
+ * fix-up (0 when this matrix does not need it or settles its carries inside the
+ * tile kernel).  ms is a host array of 2 floats.
  * A full SpMV follows the two series, so y ends up holding A*x as after
  * csr5_spmv.  csr5s_spmv_profile: the same for a single-precision handle.
  */

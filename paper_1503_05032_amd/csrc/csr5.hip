@@ -57,8 +57,26 @@ constexpr int LOOK_MAX = LOOK + LOOK_FAR;
 // nonzeros, re-reading wins up to 24 M (5-9 % of the SpMV), is level at 32 M and
 // loses beyond (3-5 %).
 constexpr int64_t LOOK_FAR_MAX_NNZ = 28 * 1000 * 1000;
+// The three instantiations of the tile kernel: cross-tile sums through the
+// auxiliary array and a second kernel; by look-behind; through the auxiliary array
+// inside the one kernel (see tile_group_of).
+constexpr int MODE_CARRY = 0, MODE_LOOK = 1, MODE_ONE = 2;
+// The one-launch form saves the second kernel (3 us and a launch) and pays for
+// one or two atomics with a return value per group of tiles, whose wavefront (and
+// with it the workgroup's LDS) stays for the answer.  Measured against the
+// two-kernel form: matrices of a few thousand tiles gain 10-20 % whatever their
+// rows look like (a dense 2000 x 2000 matrix 14.9 -> 12.0 us); with rows of 701
+// or 2000 entries throughout the gain is gone at 6 M nonzeros and turns into a
+// loss of 4-13 % at 8-21 M; matrices whose rows are short on average and that
+// take this path for a few long rows still gain at 17 M (power-law: 2.7 %) and are
+// level at 34 M.  Hence: up to ONE_LAUNCH_ANY_TILES tiles always, up to
+// ONE_LAUNCH_MAX_TILES when the average row is shorter than ONE_LAUNCH_SHORT_ROWS.
+constexpr int ONE_LAUNCH_ANY_TILES = 6144;
+constexpr int ONE_LAUNCH_MAX_TILES = 32768;
+constexpr int ONE_LAUNCH_SHORT_ROWS = 64;
 constexpr int LOOK_MIN_SIGMA = 8, LOOK_MAX_SIGMA = 32;
 constexpr bool look_sigma(int sigma) { return sigma >= LOOK_MIN_SIGMA && sigma <= LOOK_MAX_SIGMA; }
+constexpr bool one_launch_fits(int sigma, int64_t tiles) { return look_sigma(sigma) && tiles <= ONE_LAUNCH_MAX_TILES; }
 // Tiles (= wavefronts) per workgroup of the tile kernel and of the transposition,
 // chosen so the LDS buffer stays under 40 KB.
 constexpr int tile_group_waves(int sigma) { return sigma <= 16 ? 4 : (sigma <= 32 ? 2 : 1); }
@@ -116,6 +134,8 @@ inline int ceil_log2_host(int64_t v) {
     return b;
 }
 
+constexpr int MEET_STRIDE_WORDS = 1;
+
 struct Geom {
     int32_t sigma, T, W, ybits;
     int32_t p, pc;
@@ -133,6 +153,10 @@ inline Geom make_geom(int64_t nnz, int sigma) {
 }
 
 inline size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
+// one slot of the cross-tile sums of an SpMV: carry, then (one-launch form) the meeting words and the counters
+inline size_t slot_off_meet(int32_t p) { return align256((size_t(p) + 1) * 8); }
+inline size_t slot_off_arrived(int32_t p) { return slot_off_meet(p) + align256((size_t(p) + 1) * 8 * MEET_STRIDE_WORDS); }
+inline size_t slot_bytes_one(int32_t p) { return slot_off_arrived(p) + align256((size_t(p) + 1) * 4); }
 
 // ----------------------------------------------------------------------------
 // device helpers
@@ -152,6 +176,19 @@ __device__ __forceinline__ int count_le(const IT* __restrict__ a, int len, int64
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (OMEGA - 1); }
+
+// Group of tiles (= workgroup of the tile kernel) that holds a nonzero: tile t of
+// the complete tiles belongs to group t / waves, the incomplete tile is a group
+// of its own behind them.
+__device__ __forceinline__ int tile_group_of(int64_t entry, int T, int pc, int waves) {
+    const int64_t t = entry / T;
+    return t < int64_t(pc) ? int(t / waves) : (pc + waves - 1) / waves;
+}
+// "nobody has been here yet" in the meeting words of the one-launch SpMV (a NaN pattern no sum is stored as)
+constexpr uint64_t MEET_EMPTY = 0xfff8c5125eaf0001ull;
+// Distance, in 8-byte words, between the meeting words of neighbouring groups.
+constexpr int MEET_STRIDE = MEET_STRIDE_WORDS;
+__device__ __forceinline__ uint64_t* meet_at(uint64_t* meet, uint32_t g) { return meet + size_t(g) * MEET_STRIDE; }
 
 // Sets a bit of the status word.  Hundreds of thousands of threads may want the
 // same bit, and atomics on one address are served one after the other, so look
@@ -213,11 +250,19 @@ __global__ void __launch_bounds__(256)
 k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p, int pc, int group, int record_reach,
            typename Index<IT>::tp_t* __restrict__ tile_ptr, uint32_t* __restrict__ tile_head,
            uint32_t* __restrict__ wg_far, uint32_t* __restrict__ desc, size_t ndesc,
-           uint32_t* __restrict__ status) {
+           uint32_t* __restrict__ arrived, uint64_t* __restrict__ meet, size_t slot_bytes, int slots,
+           uint2* __restrict__ span, uint32_t* __restrict__ status) {
     using tp_t = typename Index<IT>::tp_t;
     size_t gid = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
     size_t stride = size_t(gridDim.x) * blockDim.x;
     for (size_t k = gid; k < ndesc; k += stride) desc[k] = 0u;
+    // the one-launch SpMV finds its counters at zero and its meeting places empty, and leaves them so
+    for (int slot = 0; slot < slots; slot++)
+        for (size_t t = gid; t <= size_t(p); t += stride) {
+            arrived[slot * (slot_bytes / 4) + t] = 0u;
+        }
+    for (int slot = 0; slot < slots; slot++)
+        for (size_t w = gid; w < (size_t(p) + 1) * MEET_STRIDE; w += stride) meet[slot * (slot_bytes / 8) + w] = MEET_EMPTY;
     if (gid == 0) *status = 0u;
     int far = 0, far_heads = 0;
     for (size_t t = gid; t <= size_t(p); t += stride) {
@@ -230,6 +275,18 @@ k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p, int pc, int grou
         int64_t head = 0;
         if (t < size_t(p) && row >= 0 && row < m) head = bnd - int64_t(row_ptr[row]);
         tile_head[t] = uint32_t(head < 0 ? 0 : (head > int64_t(0xffffffffu) ? int64_t(0xffffffffu) : head));
+        // for the one-launch SpMV: the groups of tiles that row touches (first, how many)
+        if (slots > 0) {
+            uint2 sp = {0u, 1u};
+            if (row >= 0 && row < m) {
+                const int64_t rs = int64_t(row_ptr[row]), re = int64_t(row_ptr[row + 1]);
+                if (re > rs && rs >= 0) {
+                    const int g0 = tile_group_of(rs, T, pc, group), g1 = tile_group_of(re - 1, T, pc, group);
+                    if (g1 >= g0) sp = uint2{uint32_t(g0), uint32_t(g1 - g0 + 1)};
+                }
+            }
+            span[t] = sp;
+        }
         // Can the tile kernel complete that row on its own?  The first tile of a
         // workgroup (and the workgroup of the incomplete tile) re-reads the head
         // from the previous tile's record: at most record_reach entries (LOOK_MAX,
@@ -816,6 +873,88 @@ __device__ __forceinline__ VT look_behind(const int32_t* __restrict__ last_col, 
     return wave_sum(prod);
 }
 
+// ----------------------------------------------------------------------------
+// One-launch form of the auxiliary-array path (Section 4: the sums of a row that
+// spans tiles meet in a global auxiliary array).  The tiles of a workgroup are
+// neighbours and settle the rows that cross between them through LDS.  A row that
+// crosses workgroups is settled through memory without anybody waiting.  Groups:
+// tile t of the complete tiles belongs to group t / waves, the incomplete tile is
+// a group of its own behind them; span[t] (conversion) says for the row that holds
+// tile t's first entry in which group it starts and how many groups it touches.
+//  * Two groups (nearly all such rows): each swaps its part into meet[first group]
+//    with one atomic exchange.  Whoever gets EMPTY back was first and is done;
+//    whoever gets the other's part back adds the two, stores the row and puts
+//    EMPTY back.  One memory round trip, and the value travels inside the atomic,
+//    so nothing has to be ordered.
+//  * More groups: the first group leaves its part in meet[first group], every
+//    later group its part in carry[group]; each then counts itself in at
+//    arrived[first group], and whoever finds that all the others have been there
+//    adds the parts up, in group order, stores the row and resets the two words.
+//    A part must have reached memory before its group is counted, and is read by
+//    a wavefront of another XCD, whose L2 knows nothing of it: parts and counters
+//    are written and read with device-scope atomic accesses (which pass the L2s),
+//    and the wait between "part written" and "counted" is the plain wait for the
+//    wavefront's outstanding memory operations.  (A release fence would also
+//    write back every dirty line of the L2, the rows of y included: measured once
+//    per tile, it made the kernel eleven times slower.)
+// Either way the parts are added in group order: the result does not depend on
+// who came last.
+// ----------------------------------------------------------------------------
+// A part as the 64-bit word of meet[]: a double's bits (with the one NaN pattern
+// that means EMPTY replaced by another NaN), a float's bits under a tag.
+__device__ __forceinline__ uint64_t meet_word(double v) {
+    const uint64_t b = uint64_t(__double_as_longlong(v));
+    return b == MEET_EMPTY ? 0x7ff8000000000000ull : b;
+}
+__device__ __forceinline__ uint64_t meet_word(float v) { return (1ull << 32) | uint64_t(__float_as_uint(v)); }
+template <typename VT> __device__ __forceinline__ VT meet_value(uint64_t w);
+template <> __device__ __forceinline__ double meet_value<double>(uint64_t w) { return __longlong_as_double(static_cast<long long>(w)); }
+template <> __device__ __forceinline__ float meet_value<float>(uint64_t w) { return __uint_as_float(uint32_t(w)); }
+
+__device__ __forceinline__ uint64_t swap_in(uint64_t* slot, uint64_t w) {
+    return __hip_atomic_exchange(slot, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <typename T>
+__device__ __forceinline__ void publish(T* slot, T v) {
+    __hip_atomic_store(slot, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// lane 0 of a wavefront, after publish() and wait_for_memory(): count this group
+// in at `counter`; returns how many were there before
+__device__ __forceinline__ uint32_t count_in(uint32_t* counter) {
+    return __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Barrier of the workgroup that orders LDS only: the wavefronts exchange their
+// sums through LDS, and a wavefront's atomics to memory may still be on their way.
+__device__ __forceinline__ void meet_at_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ void wait_for_memory() {
+    __builtin_amdgcn_s_waitcnt(0);          // every counter at zero: loads, stores and LDS of this wavefront are done
+    asm volatile("" ::: "memory");
+}
+
+// The whole wavefront: row R spans groups g0..g1 (three or more) and all of them have published.
+template <typename VT>
+__device__ __forceinline__ void assemble_row(const VT* piece_in, uint64_t* meet, uint32_t* arrived,
+                                             int g0, int g1, VT* __restrict__ y, uint32_t R, int m, int lane) {
+    VT sum = VT(0);
+    for (int g = g0 + 1 + lane; g <= g1; g += OMEGA)
+        sum += __hip_atomic_load(piece_in + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sum = wave_sum(sum);
+    if (lane == 0) {
+        sum = meet_value<VT>(__hip_atomic_load(meet_at(meet, g0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) + sum;
+        if (R < uint32_t(m)) y[R] = sum;
+        publish(meet_at(meet, g0), MEET_EMPTY);
+        publish(arrived + g0, 0u);
+    }
+}
+
 constexpr int TAIL_MAX_CHUNKS = (CSR5_SIGMA_MAX * OMEGA) / OMEGA + 1;   // 64-entry chunks in < one tile
 
 // Entries after the last complete tile (Section 4, last paragraph: a CSR-vector
@@ -832,6 +971,7 @@ __device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
                           const IT* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                           const VT* __restrict__ val, const VT* __restrict__ x,
                           VT* __restrict__ y, VT* __restrict__ carry_slot,
+                          VT* piece_in, uint64_t* meet, uint32_t* arrived, uint2 row_span,
                           const int32_t* __restrict__ last_col, const VT* __restrict__ last_val) {
     __shared__ VT acc[TAIL_MAX_CHUNKS];
     __shared__ int acc_row[TAIL_MAX_CHUNKS];
@@ -881,7 +1021,28 @@ __device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
     __syncthreads();
     for (int q = threadIdx.x; q < TAIL_MAX_CHUNKS; q += blockDim.x)
         if (acc_row[q] >= 0) y[acc_row[q]] = acc[q];
-    if (threadIdx.x < OMEGA) {                           // first wavefront
+    if (threadIdx.x < OMEGA && piece_in) {               // first wavefront, one-launch form: this is the last group of its first row
+        if (row_lo < m && first > 0 && row_ptr[row_lo] < first) {
+            const int g0 = int(row_span.x), g1 = g0 + int(row_span.y) - 1;
+            if (row_span.y == 2u) {
+                uint64_t other = MEET_EMPTY;
+                if (lane == 0) other = swap_in(meet_at(meet, g0), meet_word(acc_first));
+                if (lane == 0 && other != MEET_EMPTY) {
+                    y[row_lo] = meet_value<VT>(other) + acc_first;
+                    publish(meet_at(meet, g0), MEET_EMPTY);
+                }
+            } else {
+                uint32_t before = 0;
+                if (lane == 0) {
+                    publish(piece_in + g1, acc_first);
+                    wait_for_memory();
+                    before = count_in(arrived + g0);
+                }
+                if (__shfl(before, 0, OMEGA) == uint32_t(g1 - g0))
+                    assemble_row<VT>(piece_in, meet, arrived, g0, g1, y, uint32_t(row_lo), m, lane);
+            }
+        }
+    } else if (threadIdx.x < OMEGA) {                    // first wavefront
         VT carried = acc_first;
         if (last_col && row_lo < m && first > 0) {       // last_col: entries of the last complete tile, or null
             const IT rs = row_ptr[row_lo];
@@ -895,15 +1056,19 @@ __device__ void spmv_tail(int m, IT nnz, IT first, uint32_t row_first,
     }
 }
 
-template <int SIGMA, typename VT, typename IT, bool CAN_LOOK>
+template <int SIGMA, typename VT, typename IT, int MODE>
 __global__ void __launch_bounds__(TransposeShape<SIGMA>::WAVES * OMEGA)
 k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint32_t xcd_chunk, uint32_t far_mode,
        int rec_bytes, const IT* __restrict__ row_ptr, const typename Index<IT>::tp_t* __restrict__ tile_ptr,
        const uint32_t* __restrict__ tile_desc, const IT* __restrict__ eop,
        const int32_t* __restrict__ eo, const int32_t* __restrict__ col_idx,
        const VT* __restrict__ val, const VT* __restrict__ x, VT* __restrict__ y,
-       VT* __restrict__ carry, const uint32_t* __restrict__ status, const uint32_t* __restrict__ tile_head,
+       VT* __restrict__ carry, uint64_t* __restrict__ meet, uint32_t* __restrict__ arrived,
+       const uint2* __restrict__ span, const uint32_t* __restrict__ status, const uint32_t* __restrict__ tile_head,
        const int32_t* __restrict__ last_col, const VT* __restrict__ last_val) {
+    constexpr bool CAN_LOOK = MODE == MODE_LOOK;
+    constexpr bool ONE = MODE == MODE_ONE;
+    constexpr bool MEET = CAN_LOOK || ONE;      // the wavefronts of a workgroup meet at one barrier
     constexpr int T = OMEGA * SIGMA;
     constexpr int YBITS = 32 - __builtin_clz(uint32_t(T - 1));        // ceil(log2(64*sigma))
     constexpr int W = (SIGMA + SBITS + YBITS + 31) / 32;
@@ -929,6 +1094,7 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         const tp_t first_row = tile_ptr[pc] & Index<IT>::ROWMASK;
         spmv_tail<VT, IT>(m, nnz, IT(pc) * T, first_row > tp_t(m) ? uint32_t(m) : uint32_t(first_row),
                           row_ptr, col_idx, val, x, y, carry + pc,
+                          ONE ? carry : nullptr, meet, arrived, ONE ? span[pc] : uint2{0u, 1u},
                           (look && pc > 0) ? last_col + size_t((pc - 1) / WAVES) * size_t(rec_bytes / 4) : nullptr,
                           (look && pc > 0) ? last_val + size_t((pc - 1) / WAVES) * size_t(rec_bytes / int(sizeof(VT))) : nullptr);
         return;
@@ -946,7 +1112,7 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     const int tile = int(xcd_order(blockIdx.x - has_tail, nb_tiles, xcd_chunk)) * WAVES + wave;
     // (every wavefront of a tile workgroup passes exactly one barrier, see below)
     if (tile >= pc) {
-        if constexpr (CAN_LOOK) __syncthreads();
+        if constexpr (MEET) __syncthreads();
         return;
     }
 
@@ -955,6 +1121,16 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     // entries, 0 at p).  The same for every lane: scalar loads.
     const uint32_t head_len = tile_head[tile];
     const uint32_t next_head = tile_head[tile + 1];
+    // One-launch form of the auxiliary-array path: the rows that cross this tile's
+    // two boundaries (first group, number of groups), and the row of the second.
+    uint2 span_in = {0u, 1u}, span_out = {0u, 1u};
+    uint32_t out_row = 0;
+    if constexpr (ONE) {
+        span_in = span[tile];
+        span_out = span[tile + 1];
+        const typename Index<IT>::tp_t next_wide = tile_ptr[tile + 1] & Index<IT>::ROWMASK;
+        out_row = next_wide < typename Index<IT>::tp_t(m) ? uint32_t(next_wide) : 0u;
+    }
 
     // ---- look-behind, first part: the previous tile's last LOOK entries, whether
     // or not this tile turns out to need them (asking first would put a dependent
@@ -1052,7 +1228,7 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         }
     }
     if ((st & BAD_BITS) || row0_wide >= tp_t(m)) {        // rejected input: gather and store nothing
-        if constexpr (CAN_LOOK) __syncthreads();
+        if constexpr (MEET) __syncthreads();
         return;
     }
     // Does segment 0 continue a row that an earlier tile opened?  Then either this
@@ -1193,6 +1369,83 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         else if (look && cont0) head = last_sum[wave - 1];
     }
 
+    // One-launch form.  What the tiles before this one, inside the workgroup, hold
+    // of its first row comes through LDS: a tile that lies wholly inside the row
+    // passes on what it got plus its own sum, the tile the row starts in its last
+    // segment.  `outside`: the row began before the workgroup.
+    bool store_first = true, drop_last = false, pub_in = false, pub_out = false, pub_out_first = false;
+    uint32_t before_in = 0, before_out = 0;
+    uint64_t other_in = MEET_EMPTY, other_out = MEET_EMPTY;
+    VT part_in = VT(0), part_out = VT(0);
+    const int group = tile / WAVES;
+    if constexpr (ONE) {
+        __shared__ VT first_sum[WAVES];
+        __shared__ int inside_row[WAVES];
+        const bool goes_on = next_head != 0;                       // the last segment's row continues in the next tile
+        const bool last_of_group = wave == WAVES - 1 || tile + 1 >= pc;
+        const bool leaves = nseg == 1 && goes_on;                  // the tile's only segment goes on
+        // Parts that do not depend on the neighbours set out before the barrier (the
+        // answer of an atomic takes a few microseconds; the wait at the barrier and
+        // the stores of the rows pass meanwhile): the last segment of the group's
+        // last tile, and the first tile's first segment when its row ends there.
+        const bool early_out = nseg > 1 && goes_on && last_of_group;
+        const bool early_in = wave == 0 && cont0 && !leaves;
+        if (lane == 0) {
+            first_sum[wave] = nseg ? yb[0] : VT(0);
+            last_sum[wave] = nseg ? yb[nseg - 1] : VT(0);
+            inside_row[wave] = (nseg == 1 && cont0) ? 1 : 0;
+            if (early_in) {
+                part_in = first_sum[wave];
+                if (span_in.y == 2u) other_in = swap_in(meet_at(meet, span_in.x), meet_word(part_in));
+                else publish(carry + group, part_in);
+            }
+            if (early_out) {
+                part_out = last_sum[wave];
+                if (span_out.y == 2u) other_out = swap_in(meet_at(meet, group), meet_word(part_out));
+                else publish(meet_at(meet, group), meet_word(part_out));
+            }
+        }
+        meet_at_barrier();
+        bool outside = false;
+        if (cont0) {
+            outside = true;
+            for (int v = wave - 1; v >= 0; v--) {
+                if (inside_row[v]) {
+                    head += first_sum[v];
+                } else {
+                    head += last_sum[v];
+                    outside = false;
+                    break;
+                }
+            }
+        }
+        store_first = !leaves && !(cont0 && outside);
+        drop_last = goes_on;
+        // the group's part of a row that came in from outside: published where the row ends, or by the group's last tile
+        pub_in = cont0 && outside && (!leaves || last_of_group);
+        // the group's part of a row that began inside it and leaves it
+        pub_out_first = leaves && last_of_group && !(cont0 && outside);
+        pub_out = pub_out_first || early_out;
+        if (lane == 0 && (pub_in || pub_out)) {
+            const bool late_in = pub_in && !early_in, late_out = pub_out_first;
+            if (late_in || late_out) {
+                const VT whole = first_sum[wave] + head;
+                if (late_in) part_in = whole;
+                if (late_out) part_out = whole;
+            }
+            const bool count_in_row = pub_in && span_in.y != 2u, count_out_row = pub_out && span_out.y != 2u;
+            if (late_in && !count_in_row) other_in = swap_in(meet_at(meet, span_in.x), meet_word(part_in));
+            if (late_out && !count_out_row) other_out = swap_in(meet_at(meet, group), meet_word(part_out));
+            if (count_in_row || count_out_row) {
+                if (late_in && count_in_row) publish(carry + group, part_in);
+                if (late_out && count_out_row) publish(meet_at(meet, group), meet_word(part_out));
+                wait_for_memory();
+                if (count_in_row) before_in = count_in(arrived + span_in.x);
+                if (count_out_row) before_out = count_in(arrived + group);
+            }
+        }
+    }
+
     // ---- write the tile's rows.  Segment s is row tile_ptr + s, or
     // tile_ptr + empty_offset[s] when the tile holds empty rows.  Segment 0 goes
     // to the carry array when it continues an earlier tile's row.
@@ -1201,12 +1454,38 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         if (sg < nseg) {
             VT value = yb[sg];
             const uint32_t row = row0 + (dirty ? uint32_t(eo_t[sg]) : sg);
-            if (sg == 0) {
-                carry[tile] = (cont0 && !look) ? value : VT(0);
-                value += head;                             // 0 unless this tile completes the row
+            bool mine;
+            if constexpr (ONE) {
+                if (sg == 0) value += head;
+                mine = sg == 0 ? store_first : !(drop_last && sg == nseg - 1);
+            } else {
+                if (sg == 0) {
+                    carry[tile] = (cont0 && !look) ? value : VT(0);
+                    value += head;                         // 0 unless this tile completes the row
+                }
+                mine = (sg != 0 || !cont0 || look) && !(skip_last && sg == nseg - 1);
             }
-            const bool mine = (sg != 0 || !cont0 || look) && !(skip_last && sg == nseg - 1);
             if (mine && row < uint32_t(m)) y[row] = value;
+        }
+    }
+    if constexpr (ONE) {
+        // (the answers come back while the rows above are stored)
+        const uint32_t row_out = pub_out_first ? row0 : out_row;
+        if (pub_in && span_in.y == 2u) {               // two groups: the second to come stores the row
+            if (lane == 0 && other_in != MEET_EMPTY) {
+                if (row0 < uint32_t(m)) y[row0] = meet_value<VT>(other_in) + part_in;
+                publish(meet_at(meet, span_in.x), MEET_EMPTY);
+            }
+        } else if (pub_in && __shfl(before_in, 0, OMEGA) == span_in.y - 1u) {
+            assemble_row<VT>(carry, meet, arrived, int(span_in.x), int(span_in.x + span_in.y) - 1, y, row0, m, lane);
+        }
+        if (pub_out && span_out.y == 2u) {
+            if (lane == 0 && other_out != MEET_EMPTY) {
+                if (row_out < uint32_t(m)) y[row_out] = part_out + meet_value<VT>(other_out);
+                publish(meet_at(meet, group), MEET_EMPTY);
+            }
+        } else if (pub_out && __shfl(before_out, 0, OMEGA) == span_out.y - 1u) {
+            assemble_row<VT>(carry, meet, arrived, group, group + int(span_out.y) - 1, y, row_out, m, lane);
         }
     }
 }
@@ -1312,12 +1591,12 @@ k_stream_floor(int m, int pc, int sigma, int W, uint32_t nb_tiles, uint32_t xcd_
     }
 }
 
-template <int SIGMA, typename VT, typename IT, bool CAN_LOOK>
+template <int SIGMA, typename VT, typename IT, int MODE>
 hipError_t launch_spmv(const Geom& g, int m, int n, IT nnz, const IT* row_ptr,
                        const typename Index<IT>::tp_t* tile_ptr,
                        const uint32_t* tile_desc, const IT* eop, const int32_t* eo,
                        const int32_t* col_idx, const VT* val, const VT* x, VT* y,
-                       VT* carry, const uint32_t* status, const uint32_t* tile_head, const int32_t* last_col,
+                       VT* carry, uint64_t* meet, uint32_t* arrived, const uint2* span, const uint32_t* status, const uint32_t* tile_head, const int32_t* last_col,
                        const VT* last_val, bool zero_rows, uint32_t far_mode, hipStream_t s) {
     constexpr int WAVES = TransposeShape<SIGMA>::WAVES;
     uint32_t nb_tiles = uint32_t((g.pc + WAVES - 1) / WAVES);
@@ -1333,8 +1612,9 @@ hipError_t launch_spmv(const Geom& g, int m, int n, IT nnz, const IT* row_ptr,
         xcd_chunk = (int64_t(nnz) / (m > 0 ? m : 1) <= g.T / Y_LINE_ROWS) ? 1u : XCD_CHUNK;
     else if (x_bytes < XCD_CONTIGUOUS_MIN_X_BYTES)                 // x at home in every L2
         xcd_chunk = XCD_CHUNK;
-    hipLaunchKernelGGL((k_spmv<SIGMA, VT, IT, CAN_LOOK>), dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, g.p, nb_tiles, has_tail,
-                       xcd_chunk, far_mode, record_bytes(int64_t(nnz)), row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry, status, tile_head, last_col, last_val);
+    hipLaunchKernelGGL((k_spmv<SIGMA, VT, IT, MODE>), dim3(nb), dim3(WAVES * OMEGA), 0, s, m, nnz, g.pc, g.p, nb_tiles, has_tail,
+                       xcd_chunk, far_mode, record_bytes(int64_t(nnz)), row_ptr, tile_ptr, tile_desc, eop, eo, col_idx, val, x, y, carry,
+                       meet, arrived, span, status, tile_head, last_col, last_val);
     return hipGetLastError();
 }
 
@@ -1450,6 +1730,7 @@ struct csr5_handle_s {
     size_t carry_slot_bytes;
     std::atomic<uint32_t> carry_turn;
     uint32_t* tile_head;   // per tile: entries of its first row that lie before it, saturated at 32 bits
+    uint2* span;           // per tile: the groups of tiles that row touches (first, how many); NULL where the one-launch SpMV cannot run
     // CSR-order copy of the last LOOK entries of every tile group's last tile (NULL for
     // small and for large sigma): two views of one array of LAST_REC_BYTES-byte records
     int32_t* last_col;
@@ -1466,7 +1747,7 @@ struct csr5_handle_s {
 namespace {
 
 struct Layout {
-    size_t off_tile_ptr, off_tile_head, off_desc, off_eop, off_eo, off_carry, off_last, off_scan, off_wg_far, off_status, total;
+    size_t off_tile_ptr, off_tile_head, off_span, off_desc, off_eop, off_eo, off_carry, off_last, off_scan, off_wg_far, off_status, total;
     bool has_last;
     size_t ndesc, eo_cap, carry_slot_bytes;
 };
@@ -1481,10 +1762,13 @@ Layout make_layout(int32_t m, int64_t nnz, const Geom& g, bool wide) {
     size_t o = 0;
     L.off_tile_ptr = o; o += align256((size_t(g.p) + 1) * isz);
     L.off_tile_head = o; o += align256((size_t(g.p) + 1) * 4);
+    L.off_span = o;     o += one_launch_fits(g.sigma, g.p) ? align256((size_t(g.p) + 1) * 8) : 0;
     L.off_desc = o;     o += align256(L.ndesc * 4);
     L.off_eop = o;      o += align256((size_t(g.pc) + 1) * isz);
     L.off_eo = o;       o += align256(L.eo_cap * 4);
+    // one slot per SpMV in flight: carry; where the one-launch form may run, also the meeting words and the counters
     L.carry_slot_bytes = align256((size_t(g.p) + 1) * 8);
+    if (one_launch_fits(g.sigma, g.p)) L.carry_slot_bytes = slot_bytes_one(g.p);
     L.off_carry = o;    o += L.carry_slot_bytes * CARRY_SLOTS;
     L.has_last = look_sigma(g.sigma) && g.pc > 0;
     const size_t groups = (size_t(g.pc) + tile_group_waves(g.sigma) - 1) / tile_group_waves(g.sigma);
@@ -1601,6 +1885,7 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     h->carry_slot_bytes = L.carry_slot_bytes;
     h->carry_turn.store(0, std::memory_order_relaxed);
     h->tile_head = reinterpret_cast<uint32_t*>(basep + L.off_tile_head);
+    h->span = one_launch_fits(g.sigma, g.p) ? reinterpret_cast<uint2*>(basep + L.off_span) : nullptr;
     h->last_val = L.has_last ? basep + L.off_last : nullptr;                               // record + 0
     h->last_col = L.has_last ? reinterpret_cast<int32_t*>(basep + L.off_last + LOOK * 8) : nullptr;
     h->status = reinterpret_cast<uint32_t*>(basep + L.off_status);
@@ -1631,7 +1916,10 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         const size_t with_tiles = (size_t(g.p) + 1 + 255) / 256;
         n_far_wg = int(with_tiles < nb ? with_tiles : nb);
         hipLaunchKernelGGL(k_tile_ptr<IT>, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p, g.pc,
-                           tile_group_waves(g.sigma), int64_t(nnz) <= LOOK_FAR_MAX_NNZ ? LOOK_MAX : LOOK, tile_ptr, h->tile_head, wg_far, h->tile_desc, L.ndesc, h->status);
+                           tile_group_waves(g.sigma), int64_t(nnz) <= LOOK_FAR_MAX_NNZ ? LOOK_MAX : LOOK, tile_ptr, h->tile_head, wg_far, h->tile_desc, L.ndesc,
+                           reinterpret_cast<uint32_t*>(basep + L.off_carry + slot_off_arrived(g.p)),
+                           reinterpret_cast<uint64_t*>(basep + L.off_carry + slot_off_meet(g.p)), L.carry_slot_bytes,
+                           one_launch_fits(g.sigma, g.p) ? int(CARRY_SLOTS) : 0, reinterpret_cast<uint2*>(basep + L.off_span), h->status);
         e = hipGetLastError();
     }
     if (e == hipSuccess && m > 0) {   // steps 2b + 3a
@@ -1751,23 +2039,31 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, in
     const bool can_look = h->last_col && (known < 0 || !(uint32_t(known) & STATUS_NEEDS_CARRY));
     // can the look-behind of this matrix need the far part of the records
     const uint32_t far_mode = (known < 0 || (uint32_t(known) & STATUS_FAR_HEADS)) ? 1u : 0u;
+    // The auxiliary-array path in one launch: when the matrix is known to take that
+    // path, is small enough for it to pay, and the call uses the handle's own slot
+    // (whose counters the conversion cleared).
+    const bool one = !carry_mem && known >= 0 && !can_look && h->span &&
+                     (h->g.p <= ONE_LAUNCH_ANY_TILES || h->nnz / (h->m > 0 ? h->m : 1) < ONE_LAUNCH_SHORT_ROWS);
+    uint64_t* const meet = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(carry) + slot_off_meet(h->g.p));
+    uint32_t* const arrived = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(carry) + slot_off_arrived(h->g.p));
+#define ARGS h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, eop, h->eo, h->col_idx,              \
+             static_cast<const VT*>(h->val), x, y, carry, meet, arrived, h->span, h->status, h->tile_head, h->last_col, \
+             static_cast<const VT*>(h->last_val), zero_rows, far_mode, s
     if (which & LAUNCH_TILES) {
-#define X(S) case S: e = (look_sigma(S) && can_look)                                                                \
-        ? launch_spmv<S, VT, IT, look_sigma(S)>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, \
-              eop, h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y, carry, h->status, h->tile_head,          \
-              h->last_col, static_cast<const VT*>(h->last_val), zero_rows, far_mode, s)                              \
-        : launch_spmv<S, VT, IT, false>(h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc,              \
-              eop, h->eo, h->col_idx, static_cast<const VT*>(h->val), x, y, carry, h->status, h->tile_head,          \
-              h->last_col, static_cast<const VT*>(h->last_val), zero_rows, far_mode, s);                             \
+#define X(S) case S:                                                                                  \
+        if (look_sigma(S) && can_look) e = launch_spmv<S, VT, IT, look_sigma(S) ? MODE_LOOK : MODE_CARRY>(ARGS); \
+        else if (look_sigma(S) && one) e = launch_spmv<S, VT, IT, look_sigma(S) ? MODE_ONE : MODE_CARRY>(ARGS);  \
+        else e = launch_spmv<S, VT, IT, MODE_CARRY>(ARGS);                                            \
         break;
         switch (h->g.sigma) {
             CSR5_FOR_SIGMA(X)
             default: e = hipErrorInvalidValue;
         }
 #undef X
+#undef ARGS
     }
     if (e != hipSuccess) return CSR5_EHIP;
-    if ((which & LAUNCH_FIXUP) && carries && h->g.p > 0) {
+    if ((which & LAUNCH_FIXUP) && carries && !one && h->g.p > 0) {
         int ntiles = h->g.p;                                  // one thread per tile
         size_t nb = (size_t(ntiles) + 255) / 256;
         hipLaunchKernelGGL((k_spmv_fixup<VT, IT>), dim3(uint32_t(nb)), dim3(256), 0, s, h->m, ntiles,
