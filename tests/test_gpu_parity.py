@@ -224,7 +224,9 @@ def test_csr_baselines_match_oracle():
 def test_side_stream_and_graph_replay(kind):
     """csr5_spmv_ex only enqueues kernels: it runs on any stream and can be
     captured into a HIP graph; every replay must equal the eager result.  Both
-    forms of the SpMV: two kernels (a matrix with long rows) and one."""
+    ways of forming cross-tile sums: through the auxiliary array (a matrix with
+    long rows; at this size inside the tile kernel, whose meeting words and
+    counters every replay must find at rest) and by look-behind."""
     if kind == "carry_array":
         a = wl.config(4, scale=0.02)       # has empty rows, long rows and an incomplete tile
     else:
