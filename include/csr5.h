@@ -54,6 +54,11 @@ enum {
 /* csr5_convert_ex flags */
 #define CSR5_FLAG_NONE 0u
 #define CSR5_FLAG_NO_HOST_CHECK 1u /* do not wait for the device-side checks of the input: only enqueue */
+/* Measurement aids (they fix what the library otherwise chooses by the matrix's size, see csr5_spmv):
+ * a matrix whose cross-tile sums go through the auxiliary array adds them ... */
+#define CSR5_FLAG_AUX_TWO_KERNELS 2u /* ... always with the second kernel */
+#define CSR5_FLAG_AUX_ONE_KERNEL 4u  /* ... inside the tile kernel whenever the handle has the words for it
+                                        (8 <= sigma <= 32, at most 32768 tiles).  Not both; unknown bits: CSR5_EINVAL. */
 
 /* bits of the device-side status word reported by csr5_status */
 #define CSR5_STATUS_BAD_ROW_PTR 1u /* row_ptr decreasing or outside [0, nnz] */

@@ -23,6 +23,7 @@ CSR5_OMEGA, CSR5_SIGMA_MIN, CSR5_SIGMA_MAX = 64, 1, 48
 CSR5_STATIC_SCRATCH_BYTES = 4 << 20
 CSR5_STATIC_MAX_TILES = CSR5_STATIC_SCRATCH_BYTES // 8 - 1
 CSR5_FLAG_NONE, CSR5_FLAG_NO_HOST_CHECK = 0, 1
+CSR5_FLAG_AUX_TWO_KERNELS, CSR5_FLAG_AUX_ONE_KERNEL = 2, 4
 CSR5_STATUS_BAD_ROW_PTR, CSR5_STATUS_BAD_COL_IDX, CSR5_STATUS_HAS_DIRTY = 1, 2, 4
 CSR5_STATUS_HAS_EMPTY_ROWS = 8
 CSR5_ARRAY_TILE_PTR, CSR5_ARRAY_TILE_DESC, CSR5_ARRAY_EMPTY_OFFSET_PTR, CSR5_ARRAY_EMPTY_OFFSET = 0, 1, 2, 3

@@ -1730,6 +1730,7 @@ struct csr5_handle_s {
     size_t carry_slot_bytes;
     std::atomic<uint32_t> carry_turn;
     uint32_t* tile_head;   // per tile: entries of its first row that lie before it, saturated at 32 bits
+    int aux_form;          // 0: the size rule decides how the auxiliary-array path adds its sums; 1: always the second kernel; 2: inside the tile kernel wherever span exists
     uint2* span;           // per tile: the groups of tiles that row touches (first, how many); NULL where the one-launch SpMV cannot run
     // CSR-order copy of the last LOOK entries of every tile group's last tile (NULL for
     // small and for large sigma): two views of one array of LAST_REC_BYTES-byte records
@@ -1850,6 +1851,8 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     if (sigma == 0) sigma = csr5_sigma_auto(nnz, m);
     if (sigma < CSR5_SIGMA_MIN || sigma > CSR5_SIGMA_MAX) return CSR5_ERANGE;
     if (!geometry_fits(m, nnz, sigma)) return CSR5_ERANGE;
+    if ((flags & ~(CSR5_FLAG_NO_HOST_CHECK | CSR5_FLAG_AUX_TWO_KERNELS | CSR5_FLAG_AUX_ONE_KERNEL)) ||
+        ((flags & CSR5_FLAG_AUX_TWO_KERNELS) && (flags & CSR5_FLAG_AUX_ONE_KERNEL))) return CSR5_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
     Geom g = make_geom(nnz, sigma);
@@ -1885,6 +1888,7 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
     h->carry_slot_bytes = L.carry_slot_bytes;
     h->carry_turn.store(0, std::memory_order_relaxed);
     h->tile_head = reinterpret_cast<uint32_t*>(basep + L.off_tile_head);
+    h->aux_form = (flags & CSR5_FLAG_AUX_TWO_KERNELS) ? 1 : ((flags & CSR5_FLAG_AUX_ONE_KERNEL) ? 2 : 0);
     h->span = one_launch_fits(g.sigma, g.p) ? reinterpret_cast<uint2*>(basep + L.off_span) : nullptr;
     h->last_val = L.has_last ? basep + L.off_last : nullptr;                               // record + 0
     h->last_col = L.has_last ? reinterpret_cast<int32_t*>(basep + L.off_last + LOOK * 8) : nullptr;
@@ -2042,8 +2046,9 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, in
     // The auxiliary-array path in one launch: when the matrix is known to take that
     // path, is small enough for it to pay, and the call uses the handle's own slot
     // (whose counters the conversion cleared).
+    const bool one_pays = h->g.p <= ONE_LAUNCH_ANY_TILES || h->nnz / (h->m > 0 ? h->m : 1) < ONE_LAUNCH_SHORT_ROWS;
     const bool one = !carry_mem && known >= 0 && !can_look && h->span &&
-                     (h->g.p <= ONE_LAUNCH_ANY_TILES || h->nnz / (h->m > 0 ? h->m : 1) < ONE_LAUNCH_SHORT_ROWS);
+                     (h->aux_form == 2 || (h->aux_form == 0 && one_pays));
     uint64_t* const meet = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(carry) + slot_off_meet(h->g.p));
     uint32_t* const arrived = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(carry) + slot_off_arrived(h->g.p));
 #define ARGS h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, eop, h->eo, h->col_idx,              \

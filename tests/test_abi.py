@@ -131,6 +131,13 @@ def test_host_side_argument_errors(lib):
     assert rc == B.CSR5_EINVAL and not h
     assert B.csr5_free(None) == B.CSR5_OK
     assert B.csr5_strerror(B.CSR5_ERANGE).startswith("sigma out of range")
+    # flag bits nobody defined, and the two measurement flags that contradict each other (dummy aligned addresses)
+    for flags in (8, 1 << 31, B.CSR5_FLAG_AUX_TWO_KERNELS | B.CSR5_FLAG_AUX_ONE_KERNEL):
+        rc, h = B.csr5_convert_ex(10, 10, 20, 256, 256, 256, sigma=16, flags=flags, check=False, stream=0)
+        assert rc == B.CSR5_EINVAL and not h
+    hdr = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "csr5.h")).read()
+    for name in ("CSR5_FLAG_NO_HOST_CHECK", "CSR5_FLAG_AUX_TWO_KERNELS", "CSR5_FLAG_AUX_ONE_KERNEL"):
+        assert int(re.search(r"#define\s+" + name + r"\s+(\d+)u", hdr).group(1)) == getattr(B, name)
 
 
 def test_wide_variant_limits(lib):

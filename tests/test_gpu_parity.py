@@ -889,3 +889,24 @@ def test_beyond_the_one_kernel_sizes_the_second_kernel_runs():
         assert (ms_second > 1e-3) == second, (rows, ms_second)
         _check_y(d.y.cpu().numpy()[:a.m], a, ("after profile", rows))
         B.csr5_free(h)
+
+
+def test_flags_that_fix_the_form_of_the_auxiliary_array_path():
+    """CSR5_FLAG_AUX_TWO_KERNELS and CSR5_FLAG_AUX_ONE_KERNEL (measurement aids)
+    override the size rule, in both directions; y is the oracle's either way, and
+    a matrix that does not use the auxiliary array is not affected."""
+    small = wl.from_row_lengths(np.full(3000, 701), 60000, seed=2, name="small")       # rule: one kernel
+    large = wl.from_row_lengths(np.full(12000, 701), 60000, seed=3, name="large")      # rule: two
+    short = wl.from_row_lengths(np.full(20000, 20), 5000, seed=4, name="short")        # look-behind
+    for a, by_rule in ((small, False), (large, True), (short, False)):
+        for flags, second in ((B.CSR5_FLAG_NONE, by_rule), (B.CSR5_FLAG_AUX_TWO_KERNELS, a is not short),
+                              (B.CSR5_FLAG_AUX_ONE_KERNEL, False)):
+            d = DeviceCsr(a)
+            h = convert(d, sigma=16, flags=flags)
+            say("aux form", a.name, flags)
+            check_spmv(d, h, (a.name, flags))
+            _, ms_second = B.csr5_spmv_profile(h, d.x, d.y, reps=50)
+            torch.cuda.synchronize()
+            assert (ms_second > 1e-3) == second, (a.name, flags, ms_second)
+            check_spmv(d, h, (a.name, flags, "again"))
+            B.csr5_free(h)
