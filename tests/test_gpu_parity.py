@@ -910,3 +910,36 @@ def test_flags_that_fix_the_form_of_the_auxiliary_array_path():
             assert (ms_second > 1e-3) == second, (a.name, flags, ms_second)
             check_spmv(d, h, (a.name, flags, "again"))
             B.csr5_free(h)
+
+
+@pytest.mark.parametrize("kind", ["look_behind", "auxiliary_array_one_kernel"])
+def test_one_kernel_forms_add_in_a_fixed_order(kind):
+    """Both one-kernel forms add the parts of a row in an order that does not depend
+    on which wavefront finishes first: repeated calls give the same bits.  (No
+    incomplete tile here: rows cut by the 64-entry chunks inside it are added with
+    LDS atomics, and so are rows the second kernel sums with several wavefronts.)"""
+    rng = np.random.default_rng(11)
+    T = 64 * 16
+    if kind == "look_behind":
+        lens = rng.integers(1, 34, size=120_000)
+    else:
+        lens = np.where(rng.random(20_000) < 0.01, rng.integers(200, 30_000, size=20_000), rng.integers(0, 30, size=20_000))
+    lens[-1] += (-int(lens.sum())) % T
+    a = wl.from_row_lengths(lens, 40_000, seed=12, name=kind)
+    assert a.nnz % T == 0
+    d = DeviceCsr(a)
+    h = convert(d, sigma=16)
+    check_spmv(d, h, (kind,))
+    _, ms_second = B.csr5_spmv_profile(h, d.x, d.y, reps=50)
+    torch.cuda.synchronize()
+    assert ms_second < 1e-3
+    first = None
+    for call in range(8):
+        d.y.fill_(float("nan"))
+        B.csr5_spmv_ex(h, d.x, d.y)
+        torch.cuda.synchronize()
+        if first is None:
+            first = d.y.clone()
+        assert torch.equal(first.view(torch.int64), d.y.view(torch.int64)), (kind, call)
+    _check_y(first.cpu().numpy()[:a.m], a, (kind, "bits"))
+    B.csr5_free(h)
