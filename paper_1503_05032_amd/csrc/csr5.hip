@@ -62,8 +62,8 @@ constexpr int64_t LOOK_FAR_MAX_NNZ = 28 * 1000 * 1000;
 // inside the one kernel (see tile_group_of).
 constexpr int MODE_CARRY = 0, MODE_LOOK = 1, MODE_ONE = 2;
 // The one-launch form saves the second kernel (3 us and a launch) and pays for
-// one or two atomics with a return value per group of tiles, whose wavefront (and
-// with it the workgroup's LDS) stays for the answer.  Measured against the
+// one or two atomics with a return value per group of tiles (0.2-1 ns of kernel
+// time each, whenever they are sent).  Measured against the
 // two-kernel form: matrices of a few thousand tiles gain 10-20 % whatever their
 // rows look like (a dense 2000 x 2000 matrix 14.9 -> 12.0 us); with rows of 701
 // or 2000 entries throughout the gain is gone at 6 M nonzeros and turns into a
@@ -1384,10 +1384,9 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
         const bool goes_on = next_head != 0;                       // the last segment's row continues in the next tile
         const bool last_of_group = wave == WAVES - 1 || tile + 1 >= pc;
         const bool leaves = nseg == 1 && goes_on;                  // the tile's only segment goes on
-        // Parts that do not depend on the neighbours set out before the barrier (the
-        // answer of an atomic takes a few microseconds; the wait at the barrier and
-        // the stores of the rows pass meanwhile): the last segment of the group's
-        // last tile, and the first tile's first segment when its row ends there.
+        // Parts that do not depend on the neighbours set out before the barrier: the
+        // last segment of the group's last tile, and the first tile's first segment
+        // when its row ends there.
         const bool early_out = nseg > 1 && goes_on && last_of_group;
         const bool early_in = wave == 0 && cont0 && !leaves;
         if (lane == 0) {
