@@ -111,3 +111,14 @@ def tile_reference(row_ptr, m, n, t, T, sigma, col_tile, val_tile):
     assert rp[0] == 0 and rp[-1] == T
     ref = oracle.convert(r_end - r0 + 1, n, T, rp, col_tile, val_tile, 64, sigma)
     return r0, ref
+
+
+def second_kernel_ms(h, x, y, reps=100):
+    """Mean duration per call of the SpMV's second kernel (ms), 0 when none is
+    launched: the smaller of two series, so that a hiccup of the host between the
+    two event records of an empty series is not taken for a kernel (a launched
+    second kernel takes about 3e-3 ms per call, an empty series about 1e-4)."""
+    best = min(B.csr5_spmv_profile(h, x, y, reps=reps)[1] for _ in range(2))
+    torch.cuda.synchronize()
+    return best
+
