@@ -25,8 +25,8 @@ constexpr uint32_t BAD_BITS = CSR5_STATUS_BAD_ROW_PTR | CSR5_STATUS_BAD_COL_IDX;
 // kernels decide on it, and nothing in their own launches changes it.
 constexpr uint32_t STATUS_SCAN_NEEDED = 1u << 16;
 // Internal status bit: some tile (the incomplete one included) starts further
-// into a row than the tile kernel can make up for on its own, so the SpMV needs
-// its second kernel (see k_spmv and k_tile_ptr).
+// into a row than the look-behind can make up for, so the SpMV sends its
+// cross-tile sums through the auxiliary array (see k_spmv and k_tile_ptr).
 constexpr uint32_t STATUS_NEEDS_CARRY = 1u << 17;
 // Internal status bit: some first tile of a workgroup (or the incomplete tile)
 // starts more than LOOK entries into a row: the look-behind of this matrix reads
@@ -825,7 +825,12 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
 //    other tile more than a tile's length.  Such a matrix needs no second kernel.
 //  * otherwise: the auxiliary array.  Segment 0 goes to carry[tile]; the tile that
 //    holds the row's first nonzero stores the row's base value, and k_spmv_fixup
-//    adds the carries afterwards.
+//    adds the carries afterwards.  Or, for matrices where that is faster (the
+//    host decides, see ONE_LAUNCH_ANY_TILES), inside this kernel: the tiles of a
+//    workgroup settle their common rows through LDS, workgroups meet per row at a
+//    word of the auxiliary memory, and whoever comes last stores the row (see
+//    tile_group_of).
+// The third template argument (MODE) is the way: MODE_LOOK, MODE_CARRY, MODE_ONE.
 // y needs no zero-fill.  Rows that receive carries from more than one wavefront
 // of k_spmv_fixup, and rows cut by 64-entry chunks of the incomplete tile, are
 // summed with atomic adds, in whatever order they arrive: their last bits can
@@ -1446,8 +1451,9 @@ k_spmv(int m, IT nnz, int pc, int p, uint32_t nb_tiles, uint32_t has_tail, uint3
     }
 
     // ---- write the tile's rows.  Segment s is row tile_ptr + s, or
-    // tile_ptr + empty_offset[s] when the tile holds empty rows.  Segment 0 goes
-    // to the carry array when it continues an earlier tile's row.
+    // tile_ptr + empty_offset[s] when the tile holds empty rows.  In the
+    // two-kernel form segment 0 goes to the carry array when it continues an
+    // earlier tile's row.
     for (uint32_t s0 = 0; s0 < nseg; s0 += OMEGA) {
         const uint32_t sg = s0 + lane;
         if (sg < nseg) {
