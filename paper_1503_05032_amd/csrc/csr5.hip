@@ -59,7 +59,7 @@ constexpr int LOOK_MAX = LOOK + LOOK_FAR;
 constexpr int64_t LOOK_FAR_MAX_NNZ = 28 * 1000 * 1000;
 // The three instantiations of the tile kernel: cross-tile sums through the
 // auxiliary array and a second kernel; by look-behind; through the auxiliary array
-// inside the one kernel (see tile_group_of).
+// inside the one kernel (see "One-launch form of the auxiliary-array path" below).
 constexpr int MODE_CARRY = 0, MODE_LOOK = 1, MODE_ONE = 2;
 // The one-launch form saves the second kernel (3 us and a launch) and pays for
 // one or two atomics with a return value per group of tiles (0.2-1 ns of kernel
@@ -829,7 +829,7 @@ k_transpose(int pc, int n, int64_t nnz, int32_t* __restrict__ col_idx, VT* __res
 //    host decides, see ONE_LAUNCH_ANY_TILES), inside this kernel: the tiles of a
 //    workgroup settle their common rows through LDS, workgroups meet per row at a
 //    word of the auxiliary memory, and whoever comes last stores the row (see
-//    tile_group_of).
+//    "One-launch form of the auxiliary-array path" above spmv_tail).
 // The third template argument (MODE) is the way: MODE_LOOK, MODE_CARRY, MODE_ONE.
 // y needs no zero-fill.  Rows that receive carries from more than one wavefront
 // of k_spmv_fixup, and rows cut by 64-entry chunks of the incomplete tile, are
