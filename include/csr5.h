@@ -93,9 +93,9 @@ int32_t csr5_sigma_auto(int64_t nnz, int64_t m);
  * the last 32 pairs, 384 bytes, when nnz exceeds 28 million; it lets a tile finish
  * a row that began in the previous tile without a second kernel) + for 8 <= sigma <= 32
  * and at most 32768 tiles what the one-kernel form of the auxiliary-array path
- * needs (per tile: two words naming the groups of tiles its first row touches,
- * and, with each of the four auxiliary arrays, an 8-byte meeting word and a
- * counter) + the conversion's scratch
+ * needs (per tile two words naming the groups of tiles its first row touches; per
+ * group of 4 tiles, 2 for sigma > 16, and with each of the four auxiliary arrays,
+ * an 8-byte meeting word and a counter) + the conversion's scratch
  * (p_c/8192 + 1 + 8192 words) + a status word, each rounded up to 256 bytes.
  * Returns 0 for invalid arguments.
  */

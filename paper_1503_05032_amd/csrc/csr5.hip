@@ -154,9 +154,11 @@ inline Geom make_geom(int64_t nnz, int sigma) {
 
 inline size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
 // one slot of the cross-tile sums of an SpMV: carry, then (one-launch form) the meeting words and the counters
-inline size_t slot_off_meet(int32_t p) { return align256((size_t(p) + 1) * 8); }
-inline size_t slot_off_arrived(int32_t p) { return slot_off_meet(p) + align256((size_t(p) + 1) * 8 * MEET_STRIDE_WORDS); }
-inline size_t slot_bytes_one(int32_t p) { return slot_off_arrived(p) + align256((size_t(p) + 1) * 4); }
+// (meeting words and counters: one per group of tiles, the incomplete tile being a group of its own)
+inline size_t tile_groups(const Geom& g, int waves) { return (size_t(g.pc) + waves - 1) / waves + 1; }
+inline size_t slot_off_meet(const Geom& g) { return align256((size_t(g.p) + 1) * 8); }
+inline size_t slot_off_arrived(const Geom& g, int waves) { return slot_off_meet(g) + align256(tile_groups(g, waves) * 8 * MEET_STRIDE_WORDS); }
+inline size_t slot_bytes_one(const Geom& g, int waves) { return slot_off_arrived(g, waves) + align256(tile_groups(g, waves) * 4); }
 
 // ----------------------------------------------------------------------------
 // device helpers
@@ -257,12 +259,11 @@ k_tile_ptr(int m, const IT* __restrict__ row_ptr, int T, int p, int pc, int grou
     size_t stride = size_t(gridDim.x) * blockDim.x;
     for (size_t k = gid; k < ndesc; k += stride) desc[k] = 0u;
     // the one-launch SpMV finds its counters at zero and its meeting places empty, and leaves them so
-    for (int slot = 0; slot < slots; slot++)
-        for (size_t t = gid; t <= size_t(p); t += stride) {
-            arrived[slot * (slot_bytes / 4) + t] = 0u;
-        }
-    for (int slot = 0; slot < slots; slot++)
-        for (size_t w = gid; w < (size_t(p) + 1) * MEET_STRIDE; w += stride) meet[slot * (slot_bytes / 8) + w] = MEET_EMPTY;
+    const size_t groups = (size_t(pc) + group - 1) / group + 1;         // one word of each per group of tiles
+    for (int slot = 0; slot < slots; slot++) {
+        for (size_t t = gid; t < groups; t += stride) arrived[slot * (slot_bytes / 4) + t] = 0u;
+        for (size_t w = gid; w < groups * MEET_STRIDE; w += stride) meet[slot * (slot_bytes / 8) + w] = MEET_EMPTY;
+    }
     if (gid == 0) *status = 0u;
     int far = 0, far_heads = 0;
     for (size_t t = gid; t <= size_t(p); t += stride) {
@@ -1774,7 +1775,7 @@ Layout make_layout(int32_t m, int64_t nnz, const Geom& g, bool wide) {
     L.off_eo = o;       o += align256(L.eo_cap * 4);
     // one slot per SpMV in flight: carry; where the one-launch form may run, also the meeting words and the counters
     L.carry_slot_bytes = align256((size_t(g.p) + 1) * 8);
-    if (one_launch_fits(g.sigma, g.p)) L.carry_slot_bytes = slot_bytes_one(g.p);
+    if (one_launch_fits(g.sigma, g.p)) L.carry_slot_bytes = slot_bytes_one(g, tile_group_waves(g.sigma));
     L.off_carry = o;    o += L.carry_slot_bytes * CARRY_SLOTS;
     L.has_last = look_sigma(g.sigma) && g.pc > 0;
     const size_t groups = (size_t(g.pc) + tile_group_waves(g.sigma) - 1) / tile_group_waves(g.sigma);
@@ -1926,8 +1927,8 @@ static int convert_impl(int32_t m, int32_t n, IT nnz, const IT* row_ptr, int32_t
         n_far_wg = int(with_tiles < nb ? with_tiles : nb);
         hipLaunchKernelGGL(k_tile_ptr<IT>, dim3(uint32_t(nb)), dim3(256), 0, s, m, row_ptr, g.T, g.p, g.pc,
                            tile_group_waves(g.sigma), int64_t(nnz) <= LOOK_FAR_MAX_NNZ ? LOOK_MAX : LOOK, tile_ptr, h->tile_head, wg_far, h->tile_desc, L.ndesc,
-                           reinterpret_cast<uint32_t*>(basep + L.off_carry + slot_off_arrived(g.p)),
-                           reinterpret_cast<uint64_t*>(basep + L.off_carry + slot_off_meet(g.p)), L.carry_slot_bytes,
+                           reinterpret_cast<uint32_t*>(basep + L.off_carry + slot_off_arrived(g, tile_group_waves(g.sigma))),
+                           reinterpret_cast<uint64_t*>(basep + L.off_carry + slot_off_meet(g)), L.carry_slot_bytes,
                            one_launch_fits(g.sigma, g.p) ? int(CARRY_SLOTS) : 0, reinterpret_cast<uint2*>(basep + L.off_span), h->status);
         e = hipGetLastError();
     }
@@ -2054,8 +2055,8 @@ static int spmv_launch_it(csr5_handle_t h, const VT* x, VT* y, hipStream_t s, in
     const bool one_pays = h->g.p <= ONE_LAUNCH_ANY_TILES || h->nnz / (h->m > 0 ? h->m : 1) < ONE_LAUNCH_SHORT_ROWS;
     const bool one = !carry_mem && known >= 0 && !can_look && h->span &&
                      (h->aux_form == 2 || (h->aux_form == 0 && one_pays));
-    uint64_t* const meet = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(carry) + slot_off_meet(h->g.p));
-    uint32_t* const arrived = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(carry) + slot_off_arrived(h->g.p));
+    uint64_t* const meet = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(carry) + slot_off_meet(h->g));
+    uint32_t* const arrived = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(carry) + slot_off_arrived(h->g, tile_group_waves(h->g.sigma)));
 #define ARGS h->g, h->m, h->n, IT(h->nnz), row_ptr, tile_ptr, h->tile_desc, eop, h->eo, h->col_idx,              \
              static_cast<const VT*>(h->val), x, y, carry, meet, arrived, h->span, h->status, h->tile_head, h->last_col, \
              static_cast<const VT*>(h->last_val), zero_rows, far_mode, s

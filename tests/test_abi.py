@@ -96,7 +96,7 @@ def test_workspace_bytes(lib):
     p, pc = -(-nnz // T), nnz // T
     W = oracle.desc_words(64, sigma)
     need = (p + 1) * 4 + pc * W * 64 * 4 + (pc + 1) * 4 + min(m + pc, pc * T) * 4 + 4 * (p + 1) * 8 + 4
-    need += 4 * (p + 1) * (8 + 4)          # one-launch SpMV (8 <= sigma <= 32, up to 32768 tiles): a meeting word and a counter per tile, four times
+    need += 4 * (-(-pc // 4) + 1) * (8 + 4)    # one-launch SpMV (8 <= sigma <= 32, up to 32768 tiles): a meeting word and a counter per group of 4 tiles (+ the incomplete one), four times
     need += (p + 1) * 8                    # ... and per tile the groups of tiles its first row touches
     need += -(-pc // 4) * 160 * (4 + 8)    # copy of the last 160 entries of every 4th tile and of the last (8 <= sigma <= 16)
     need += (p + 1) * 4                    # per tile: how far into its first row it starts
@@ -107,7 +107,7 @@ def test_workspace_bytes(lib):
     T24 = 64 * 24
     p24, pc24 = -(-nnz // T24), nnz // T24
     need24 = ((p24 + 1) * 4 + pc24 * oracle.desc_words(64, 24) * 64 * 4 + (pc24 + 1) * 4 + min(m + pc24, pc24 * T24) * 4
-              + 4 * (p24 + 1) * (8 + 8 + 4) + (p24 + 1) * 8 + 4 + -(-pc24 // 2) * 160 * (4 + 8) + (p24 + 1) * 4 + 8192 * 4)
+              + 4 * ((p24 + 1) * 8 + (-(-pc24 // 2) + 1) * (8 + 4)) + (p24 + 1) * 8 + 4 + -(-pc24 // 2) * 160 * (4 + 8) + (p24 + 1) * 4 + 8192 * 4)
     assert need24 <= B.csr5_workspace_bytes(m, nnz, 24) <= need24 + 23 * 256
     # beyond 28 million nonzeros the copies hold 32 entries
     mb, nb = 3_000_000, 40_000_000
@@ -148,7 +148,7 @@ def test_wide_variant_limits(lib):
     W = oracle.desc_words(64, sigma)
     need = (p + 1) * 8 + pc * W * 64 * 4 + (pc + 1) * 8 + min(m + pc, pc * T) * 4 + 4 * (p + 1) * 8 + 4
     need += -(-pc // 4) * 160 * (4 + 8) + (p + 1) * 4 + 8192 * 4
-    need += (p + 1) * (4 * (8 + 4) + 8)    # one-launch SpMV: meeting words, counters, groups per row
+    need += 4 * (-(-pc // 4) + 1) * (8 + 4) + (p + 1) * 8    # one-launch SpMV: meeting words and counters per group of tiles, groups per row
     got = B.csr5l_workspace_bytes(m, nnz, sigma)
     assert need <= got <= need + 23 * 256
     # beyond 2^31 nonzeros; the limit is the number of tiles (2^26 - 5)
