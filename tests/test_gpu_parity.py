@@ -936,3 +936,38 @@ def test_one_kernel_forms_add_in_a_fixed_order(kind):
         assert torch.equal(first.view(torch.int64), d.y.view(torch.int64)), (kind, call)
     _check_y(first.cpu().numpy()[:a.m], a, (kind, "bits"))
     B.csr5_free(h)
+
+
+@pytest.mark.parametrize("seed,cases", [(5000, 150), (77000, 150)])
+def test_random_matrices_with_rows_across_tile_groups(seed, cases):
+    """Random small matrices in which rows of every length up to several groups of
+    tiles are mixed with short and empty ones, at random tile heights 8..32, in
+    both index widths: the auxiliary-array path inside the tile kernel.  Two calls
+    with different x on every handle."""
+    for case in range(cases):
+        rng = np.random.default_rng(seed + case)
+        sigma = int(rng.integers(8, 33))
+        T = 64 * sigma
+        G = T * (4 if sigma <= 16 else 2)
+        m = int(rng.integers(1, 400))
+        kind = case % 5
+        base = rng.integers(0, 40, size=m)
+        if kind == 0:
+            lens = np.where(rng.random(m) < 0.1, rng.integers(150, 4 * G, size=m), base)
+        elif kind == 1:
+            lens = np.where(rng.random(m) < 0.3, rng.integers(G - 3, G + 4, size=m), base)
+        elif kind == 2:
+            lens = np.where(rng.random(m) < 0.2, rng.integers(1, 6, size=m) * G + rng.integers(-2, 3, size=m), base)
+        elif kind == 3:
+            lens = np.where(rng.random(m) < 0.3, rng.integers(T - 2, 3 * T, size=m), np.where(rng.random(m) < 0.5, 0, base))
+        else:
+            lens = rng.integers(100, 6 * T, size=m)
+        lens = np.maximum(lens, 0)
+        n = int(max(lens.max(), 200)) + int(rng.integers(0, 500))
+        a = wl.from_row_lengths(lens, n, seed=seed + case, name=f"groups{case}")
+        d = DeviceCsr(a, wide=bool(case % 2))
+        say("case", case, "kind", kind, "sigma", sigma, "m", a.m, "nnz", a.nnz, "wide", d.wide)
+        h = convert(d, sigma=sigma)
+        for call in range(2):
+            check_spmv(d, h, (a.name, sigma, call), x=rng.standard_normal(a.n))
+        B.csr5_free(h)
